@@ -1,0 +1,254 @@
+/*
+ * pipelive.h - C ABI of the MI355X (gfx950) hot path of PipeLive:
+ * paged-attention decode over a resizable, block-list-indirected KV cache,
+ * in-place KV resize/compaction, and incremental KV patching.
+ *
+ * Conventions
+ *  - Plain C, every call returns int32_t: PIPELIVE_OK (0) or a negative
+ *    PIPELIVE_E_* code.  Nothing throws.
+ *  - "DEVICE" pointers are HIP device addresses on the current device,
+ *    "HOST" pointers are ordinary host memory.  The caller owns every device
+ *    buffer; the library never allocates or frees device memory (it keeps one
+ *    small pinned host buffer per handle).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it unless the text says they synchronise.
+ *  - Faults found on the device (a block id out of range in a table or a
+ *    patch) never touch memory: the access is skipped and a sticky status
+ *    word in the region's device state is set; pipelive_kv_read_state
+ *    returns it.
+ *  - A handle is not re-entrant; distinct handles are independent.  Calls on
+ *    one handle must be issued in stream order on one stream.
+ *
+ * KV region layout (paper Sec. 5.1 "KV Cache Resizing", Sec. 5.2 "Layer
+ * Stacking"): the cache is a *block list* of independently placed physical
+ * blocks; nothing assumes address = base + id * stride.  Physical block `id`
+ * of layer group `g = layer / stack_k` is at block_list[g * capacity + id];
+ * layer `l` occupies bytes [(l % stack_k) * blk, +blk) of it, where
+ *     blk = 2 (K,V) * num_kv_heads * block_tokens * head_dim * 2 bytes (bf16).
+ * In-block layout 0 (PIPELIVE_LAYOUT_D8), element offsets in bf16 units:
+ *     K[g][t][d] at ((g * (D/8) + d/8) * bs + t) * 8 + d % 8
+ *     V[g][t][d] at Hkv*bs*D + (g * D + d) * bs + t
+ * i.e. K is stored as [Hkv][D/8][bs][8] (16-byte token vectors, token-major
+ * inside a d-slice) and V as [Hkv][D][bs] (token-contiguous), so that both
+ * MFMA operands of the decode kernel are fetched with fully coalesced loads.
+ */
+#ifndef PIPELIVE_H
+#define PIPELIVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIPELIVE_OK 0
+#define PIPELIVE_E_INVAL (-1)      /* bad argument, shape or alignment */
+#define PIPELIVE_E_INFEASIBLE (-2) /* shrink below the number of live blocks (Alg. 1, phase 1) */
+#define PIPELIVE_E_NOSPACE (-3)    /* grow beyond capacity, workspace or patch buffer too small */
+#define PIPELIVE_E_BUSY (-4)       /* resize while dirty bits are pending */
+#define PIPELIVE_E_RANGE (-5)      /* block id or layer out of range / table entry not live */
+#define PIPELIVE_E_HIP (-6)        /* HIP runtime error, see pipelive_last_hip_error() */
+
+#define PIPELIVE_LAYOUT_D8 0
+#define PIPELIVE_DTYPE_BF16 0
+#define PIPELIVE_OUT_F32 0
+#define PIPELIVE_OUT_BF16 1
+#define PIPELIVE_MAX_PATCH_LAYERS 128
+#define PIPELIVE_MAX_TABLES 8
+#define PIPELIVE_PATCH_MAGIC 0x564B4C50u /* bytes 'P','L','K','V' */
+#define PIPELIVE_PATCH_VERSION 1u
+
+typedef struct pipelive_kv pipelive_kv_t;
+
+/* Description of one KV region (HOST struct, copied by pipelive_kv_create). */
+typedef struct {
+  int32_t num_layers;      /* L: layers resident in this region */
+  int32_t num_q_heads;     /* Hq */
+  int32_t num_kv_heads;    /* Hkv, divides Hq; query head h reads KV head h / (Hq/Hkv) */
+  int32_t head_dim;        /* D: 64 or 128 */
+  int32_t block_tokens;    /* bs: 16 or 32 tokens per block */
+  int32_t stack_k;         /* layers per physical block (Sec. 5.2); 1 = one pool per layer */
+  int32_t dtype;           /* PIPELIVE_DTYPE_BF16 */
+  int32_t in_block_layout; /* PIPELIVE_LAYOUT_D8 */
+  int64_t num_blocks;      /* B: valid ids are 0 .. B-1 */
+  int64_t capacity_blocks; /* entries per group in block_list, B <= capacity < 2^31 */
+  const uint64_t *block_list; /* DEVICE [ceil(L/stack_k)][capacity]: block addresses, 256-B aligned */
+  uint8_t *live_bitmap;    /* DEVICE, pipelive_bitmap_bytes(capacity): bit i = byte i>>3, bit i&7;
+                              maintained by the caller's block manager, updated by resize */
+  uint8_t *dirty_bitmap;   /* DEVICE, same size and bit order; maintained by the library; zeroed by the caller at start */
+  void *dev_state;         /* DEVICE, pipelive_kv_state_bytes(capacity) bytes, 256-B aligned,
+                              zeroed by the caller before pipelive_kv_create */
+} pipelive_kv_desc_t;
+
+/* bytes of one bitmap for `capacity_blocks` ids (a whole number of 64-bit words) */
+size_t pipelive_bitmap_bytes(int64_t capacity_blocks);
+/* bytes of the per-region device state (counters, status, drain snapshot) */
+size_t pipelive_kv_state_bytes(int64_t capacity_blocks);
+
+/* Create / destroy the host-side handle.  No device work. */
+int32_t pipelive_kv_create(const pipelive_kv_desc_t *desc, pipelive_kv_t **out);
+void pipelive_kv_destroy(pipelive_kv_t *kv);
+/* current B of the region */
+int64_t pipelive_kv_num_blocks(const pipelive_kv_t *kv);
+
+/* -------------------------------------------------------------------------
+ * 1. Decode attention of ONE layer (Sec. 2 "LLM Inference": a decode step
+ * reads the whole cached K/V of every running sequence; Sec. 5.1: blocks are
+ * resolved through the block table and the block list at kernel time).
+ *
+ *   out[s][h][:] = sum_j softmax_j(scale * <q[s][h], K_j>) V_j ,  j < ctx_lens[s]
+ * with token j in block block_table[s][j / bs], slot j % bs, KV head
+ * h / (Hq/Hkv); bf16 inputs, fp32 accumulation.  No mask.  ctx_lens[s] == 0
+ * gives a zero row.  Slots >= ctx_lens[s] and free blocks are never read into
+ * the result (they may hold NaN).
+ *
+ * q            DEVICE bf16 [num_seqs][Hq][D], 16-B aligned
+ * out          DEVICE [num_seqs][Hq][D], fp32 (PIPELIVE_OUT_F32) or bf16
+ * block_table  DEVICE int32 [num_seqs][table_stride] of block ids; only the
+ *              first ceil(ctx/bs) entries of a row are read
+ * ctx_lens     DEVICE int32 [num_seqs]
+ * max_ctx      HOST upper bound on ctx_lens (sizes the launch; sequences
+ *              longer than it are truncated to it and flagged E_RANGE)
+ * scale        <= 0 selects 1/sqrt(D)
+ * split_tokens tokens per workgroup (a multiple of 64); 0 = library
+ *              heuristic.  For equal split_tokens the result is bit-identical
+ *              whatever the physical placement of the blocks.
+ * workspace    DEVICE, >= pipelive_paged_attn_workspace_bytes(...), 256-B
+ *              aligned; holds the per-split partial results
+ * Asynchronous on `stream`.
+ */
+int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                   int32_t out_dtype, const int32_t *block_table,
+                                   int32_t table_stride, const int32_t *ctx_lens, int32_t num_seqs,
+                                   int32_t max_ctx, float scale, int32_t split_tokens,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
+                                           int32_t max_ctx, int32_t split_tokens);
+/* the split size the heuristic would pick for this launch */
+int32_t pipelive_paged_attn_pick_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx);
+
+/* -------------------------------------------------------------------------
+ * 2. ResizeKV(B) with compaction (Sec. 4.2 primitive ResizeKV; Alg. 1 phases
+ * 1-2 and 5; Sec. 5.1).
+ *
+ * Shrink (new_num_blocks < B): if more than new_num_blocks blocks are live
+ * the call returns PIPELIVE_E_INFEASIBLE; if a dirty bit is pending,
+ * PIPELIVE_E_BUSY; if a used table entry is out of range or not live,
+ * PIPELIVE_E_RANGE - in all three cases no byte of pool, tables or bitmaps
+ * changes.  Otherwise the live blocks with id >= new_num_blocks, in
+ * ascending order, move into the free ids below new_num_blocks, in ascending
+ * order (every layer's bytes are copied), the live bitmap and every used
+ * table entry follow, and B becomes new_num_blocks.  Blocks that stay keep
+ * their ids; bytes below new_num_blocks that no move targets are untouched.
+ * Grow (new_num_blocks > B, <= capacity; the caller has filled the new
+ * block_list entries): B becomes new_num_blocks, the new ids are not live, no
+ * data moves.
+ *
+ * block_tables  HOST array of num_tables DEVICE pointers, int32 [rows][stride]
+ * table_rows, table_strides  HOST int32 [num_tables]
+ * table_used    HOST array of num_tables DEVICE pointers, int32 [rows]: number
+ *               of valid leading entries of each row (e.g. ceil(ctx/bs))
+ * remap_out     DEVICE int32 [old B] or NULL: new id of every old id
+ *               (identity if it stayed, -1 if it was not live)
+ * result        HOST; filled before returning
+ * workspace     DEVICE >= pipelive_kv_resize_workspace_bytes(kv), 256-B aligned
+ * The call synchronises `stream` once (the feasibility verdict is a host
+ * decision) and is complete on the stream order when it returns.
+ */
+typedef struct {
+  int64_t n_live, n_moved, old_num_blocks, new_num_blocks;
+  int32_t status; /* same as the return value */
+  int32_t reserved;
+} pipelive_resize_result_t;
+
+int32_t pipelive_kv_resize(pipelive_kv_t *kv, int64_t new_num_blocks, int32_t *const *block_tables,
+                           const int32_t *table_rows, const int32_t *table_strides,
+                           const int32_t *const *table_used, int32_t num_tables,
+                           int32_t *remap_out, pipelive_resize_result_t *result, void *workspace,
+                           size_t workspace_bytes, void *stream);
+size_t pipelive_kv_resize_workspace_bytes(const pipelive_kv_t *kv);
+
+/* MaxBlocks(i, L) = floor((M_i * u - L * W) / (L * P))  (Alg. 1); host arithmetic only. */
+int64_t pipelive_max_blocks(double mem_bytes, double util, int64_t layers,
+                            double weight_bytes_per_layer, double block_bytes_per_layer);
+
+/* -------------------------------------------------------------------------
+ * 3. Incremental KV patching (Sec. 6.1 "KV Migration with KV Patch").
+ * One dirty bit per block id, shared by all layers of the region (a decode
+ * step writes the same slot in every layer).
+ *
+ * mark_dirty: B[id] <- 1 for the n ids in block_ids (DEVICE int32), and
+ * n_acc += n_tokens (the tokens scheduled in that step).  Asynchronous.
+ */
+int32_t pipelive_kv_mark_dirty(pipelive_kv_t *kv, const int32_t *block_ids, int32_t n,
+                               int64_t n_tokens, void *stream);
+
+/* 64-byte header at patch_buf[0] (little endian). */
+typedef struct {
+  uint32_t magic, version;
+  uint32_t n_blocks; /* ids carried by this patch */
+  uint32_t n_layers;
+  uint64_t block_bytes;    /* blk */
+  uint64_t n_acc_tokens;   /* tokens this patch acknowledges */
+  uint64_t payload_offset; /* round_up(64 + 4 * max_blocks, 256) */
+  uint32_t max_blocks;     /* capacity of the id list */
+  uint32_t more_pending;   /* 1 if dirty bits were left behind */
+  uint8_t pad[16];
+} pipelive_patch_hdr_t;
+
+/* number of blocks a patch buffer of `capacity` bytes can carry:
+ * min(B, floor((capacity - 320) / (4 + n_layers * blk))) */
+int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, size_t capacity);
+
+/* collect: atomically take the dirty set D (ascending ids, at most
+ * max_blocks of them - the lowest; the others stay set and more_pending = 1),
+ * clear exactly those bits, and gather into patch_buf
+ *     header | int32 ids[max_blocks] | pad to 256 B | payload[r][i][blk]
+ * where payload[r][i] is the verbatim K-then-V bytes of block ids[r] in layer
+ * layers[i].  n_acc travels in the header (and restarts from 0) only when the
+ * drain empties the bitmap.  A mark racing with the drain lands in this patch
+ * or the next one, never nowhere.
+ *
+ * layers         HOST int32 [n_layers] (region-local layer indices, patch order)
+ * patch_buf      DEVICE, 256-B aligned, patch_capacity_bytes
+ * hdr_host_copy  HOST (pinned) or NULL; filled by an async copy on `stream`
+ * Asynchronous; no host round trip (the number of dirty blocks stays on the device).
+ */
+int32_t pipelive_kv_patch_collect(pipelive_kv_t *src, const int32_t *layers, int32_t n_layers,
+                                  void *patch_buf, size_t patch_capacity_bytes,
+                                  pipelive_patch_hdr_t *hdr_host_copy, void *stream);
+
+/* apply: write every entry of the patch into block dst_block_map[id]
+ * (identity when NULL) of layer dst_layers[i] of `dst`, then
+ * T_applied += n_acc_tokens.  A header that does not match (magic, version,
+ * n_layers, block_bytes) or an id outside dst sets the status word and skips
+ * the entry.  Asynchronous.
+ *
+ * dst_layers     HOST int32 [n_layers]
+ * dst_block_map  DEVICE int32 indexed by source id, or NULL
+ */
+int32_t pipelive_kv_patch_apply(pipelive_kv_t *dst, const int32_t *dst_layers, int32_t n_layers,
+                                const void *patch_buf, const int32_t *dst_block_map, void *stream);
+
+/* Counters and status of a region; synchronises `stream`. */
+typedef struct {
+  uint64_t n_acc;     /* tokens marked since the last complete drain */
+  uint64_t t_applied; /* tokens acknowledged by applied patches (T_applied) */
+  int32_t status;     /* sticky device status: PIPELIVE_OK or the first PIPELIVE_E_* seen */
+  int32_t reserved;
+} pipelive_kv_state_t;
+int32_t pipelive_kv_read_state(pipelive_kv_t *kv, pipelive_kv_state_t *out, void *stream);
+/* clear the sticky status (asynchronous) */
+int32_t pipelive_kv_clear_status(pipelive_kv_t *kv, void *stream);
+
+const char *pipelive_strerror(int32_t code);
+/* text of the last HIP error seen by the calling thread ("" if none) */
+const char *pipelive_last_hip_error(void);
+/* 1 if the current device is a gfx950, else 0 */
+int32_t pipelive_device_ok(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIPELIVE_H */

@@ -1,0 +1,345 @@
+"""Thin ctypes binding of libpipelive.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (without the
+``pipelive_`` prefix being dropped: ``pipelive_paged_attn_decode`` etc.).
+Tensors are passed as raw device addresses, the stream as the current torch
+stream's handle.  :class:`KVRegion` is plumbing: it owns the torch
+allocations of one KV region (block arenas, block list, bitmaps, device
+state) and the library handle.  Nothing here computes: if the HIP library
+cannot be loaded the import fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+from . import build as _build
+
+OK, E_INVAL, E_INFEASIBLE, E_NOSPACE, E_BUSY, E_RANGE, E_HIP = 0, -1, -2, -3, -4, -5, -6
+LAYOUT_D8 = 0
+OUT_F32, OUT_BF16 = 0, 1
+MAX_PATCH_LAYERS = 128
+MAX_TABLES = 8
+PATCH_MAGIC = 0x564B4C50
+
+EXPORTS = [
+    "pipelive_bitmap_bytes", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
+    "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_workspace_bytes",
+    "pipelive_paged_attn_pick_split", "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
+    "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
+    "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
+    "pipelive_kv_clear_status", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
+]
+
+
+class KVDesc(C.Structure):
+    _fields_ = [
+        ("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+        ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("stack_k", C.c_int32),
+        ("dtype", C.c_int32), ("in_block_layout", C.c_int32),
+        ("num_blocks", C.c_int64), ("capacity_blocks", C.c_int64),
+        ("block_list", C.c_void_p), ("live_bitmap", C.c_void_p), ("dirty_bitmap", C.c_void_p),
+        ("dev_state", C.c_void_p),
+    ]
+
+
+class ResizeResult(C.Structure):
+    _fields_ = [("n_live", C.c_int64), ("n_moved", C.c_int64), ("old_num_blocks", C.c_int64),
+                ("new_num_blocks", C.c_int64), ("status", C.c_int32), ("reserved", C.c_int32)]
+
+
+class PatchHdr(C.Structure):
+    _fields_ = [("magic", C.c_uint32), ("version", C.c_uint32), ("n_blocks", C.c_uint32),
+                ("n_layers", C.c_uint32), ("block_bytes", C.c_uint64), ("n_acc_tokens", C.c_uint64),
+                ("payload_offset", C.c_uint64), ("max_blocks", C.c_uint32),
+                ("more_pending", C.c_uint32), ("pad", C.c_uint8 * 16)]
+
+
+class KVState(C.Structure):
+    _fields_ = [("n_acc", C.c_uint64), ("t_applied", C.c_uint64), ("status", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+assert C.sizeof(PatchHdr) == 64
+
+_lib = None
+
+
+def load(path: str | None = None):
+    """dlopen the HIP library (building it first only if no built library exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = path or _build.LIB
+    if not os.path.exists(path):
+        _build.build_lib()
+    L = C.CDLL(path)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    L.pipelive_bitmap_bytes.restype = sz
+    L.pipelive_bitmap_bytes.argtypes = [i64]
+    L.pipelive_kv_state_bytes.restype = sz
+    L.pipelive_kv_state_bytes.argtypes = [i64]
+    L.pipelive_kv_create.restype = i32
+    L.pipelive_kv_create.argtypes = [C.POINTER(KVDesc), C.POINTER(vp)]
+    L.pipelive_kv_destroy.restype = None
+    L.pipelive_kv_destroy.argtypes = [vp]
+    L.pipelive_kv_num_blocks.restype = i64
+    L.pipelive_kv_num_blocks.argtypes = [vp]
+    L.pipelive_paged_attn_decode.restype = i32
+    L.pipelive_paged_attn_decode.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, i32, i32, C.c_float,
+                                             i32, vp, sz, vp]
+    L.pipelive_paged_attn_workspace_bytes.restype = sz
+    L.pipelive_paged_attn_workspace_bytes.argtypes = [vp, i32, i32, i32]
+    L.pipelive_paged_attn_pick_split.restype = i32
+    L.pipelive_paged_attn_pick_split.argtypes = [vp, i32, i32]
+    L.pipelive_kv_resize.restype = i32
+    L.pipelive_kv_resize.argtypes = [vp, i64, vp, vp, vp, vp, i32, vp, C.POINTER(ResizeResult), vp,
+                                     sz, vp]
+    L.pipelive_kv_resize_workspace_bytes.restype = sz
+    L.pipelive_kv_resize_workspace_bytes.argtypes = [vp]
+    L.pipelive_max_blocks.restype = i64
+    L.pipelive_max_blocks.argtypes = [C.c_double, C.c_double, i64, C.c_double, C.c_double]
+    L.pipelive_kv_mark_dirty.restype = i32
+    L.pipelive_kv_mark_dirty.argtypes = [vp, vp, i32, i64, vp]
+    L.pipelive_patch_max_blocks.restype = i64
+    L.pipelive_patch_max_blocks.argtypes = [vp, i32, sz]
+    L.pipelive_kv_patch_collect.restype = i32
+    L.pipelive_kv_patch_collect.argtypes = [vp, vp, i32, vp, sz, vp, vp]
+    L.pipelive_kv_patch_apply.restype = i32
+    L.pipelive_kv_patch_apply.argtypes = [vp, vp, i32, vp, vp, vp]
+    L.pipelive_kv_read_state.restype = i32
+    L.pipelive_kv_read_state.argtypes = [vp, C.POINTER(KVState), vp]
+    L.pipelive_kv_clear_status.restype = i32
+    L.pipelive_kv_clear_status.argtypes = [vp, vp]
+    L.pipelive_strerror.restype = C.c_char_p
+    L.pipelive_strerror.argtypes = [i32]
+    L.pipelive_last_hip_error.restype = C.c_char_p
+    L.pipelive_device_ok.restype = i32
+    _lib = L
+    return L
+
+
+class PipeliveError(RuntimeError):
+    def __init__(self, rc: int):
+        L = load()
+        msg = L.pipelive_strerror(rc).decode()
+        if rc == E_HIP:
+            msg += ": " + L.pipelive_last_hip_error().decode()
+        super().__init__(f"pipelive error {rc}: {msg}")
+        self.rc = rc
+
+
+def _check(rc: int) -> int:
+    if rc != OK:
+        raise PipeliveError(rc)
+    return rc
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _p(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _i32_array(vals):
+    vals = [int(v) for v in vals]
+    return (C.c_int32 * max(len(vals), 1))(*vals)
+
+
+# ---- the entry points, same names as the C ABI ---------------------------------
+
+def pipelive_paged_attn_decode(kv: "KVRegion", layer, q, out, block_table, ctx_lens, max_ctx=0,
+                               scale=0.0, split_tokens=0, workspace=None, check=True):
+    """q bf16 [S][Hq][D]; out fp32 or bf16 [S][Hq][D]; block_table int32 [S][stride]; ctx_lens int32 [S]."""
+    L = load()
+    S = int(ctx_lens.shape[0])
+    out_dtype = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    stride = int(block_table.shape[1])
+    if workspace is None:
+        workspace = kv.attn_workspace(S, max_ctx if max_ctx > 0 else stride * kv.bs, split_tokens)
+    rc = L.pipelive_paged_attn_decode(kv.handle, int(layer), _p(q), _p(out), out_dtype,
+                                      _p(block_table), stride, _p(ctx_lens), S, int(max_ctx),
+                                      float(scale), int(split_tokens), _p(workspace),
+                                      workspace.numel() * workspace.element_size(), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_kv_resize(kv: "KVRegion", new_num_blocks, tables=(), used=(), remap_out=None,
+                       workspace=None):
+    """Returns (rc, ResizeResult).  tables: int32 device tensors [rows][stride], remapped in place."""
+    L = load()
+    n = len(tables)
+    tp = (C.c_void_p * max(n, 1))(*[t.data_ptr() for t in tables])
+    up = (C.c_void_p * max(n, 1))(*[u.data_ptr() for u in used])
+    rows = _i32_array([t.shape[0] for t in tables])
+    strides = _i32_array([t.shape[1] for t in tables])
+    if workspace is None:
+        workspace = kv.resize_workspace()
+    res = ResizeResult()
+    rc = L.pipelive_kv_resize(kv.handle, int(new_num_blocks), tp, rows, strides, up, n,
+                              _p(remap_out), C.byref(res), _p(workspace), workspace.numel(),
+                              _stream())
+    return rc, res
+
+
+def pipelive_kv_mark_dirty(kv: "KVRegion", block_ids, n_tokens, check=True):
+    L = load()
+    rc = L.pipelive_kv_mark_dirty(kv.handle, _p(block_ids), int(block_ids.numel()), int(n_tokens),
+                                  _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_kv_patch_collect(src: "KVRegion", layers, patch_buf, hdr_host=None, check=True):
+    L = load()
+    la = _i32_array(layers)
+    rc = L.pipelive_kv_patch_collect(src.handle, la, len(layers), _p(patch_buf), patch_buf.numel(),
+                                     _p(hdr_host), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_kv_patch_apply(dst: "KVRegion", dst_layers, patch_buf, dst_block_map=None, check=True):
+    L = load()
+    la = _i32_array(dst_layers)
+    rc = L.pipelive_kv_patch_apply(dst.handle, la, len(dst_layers), _p(patch_buf),
+                                   _p(dst_block_map), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_patch_max_blocks(kv: "KVRegion", n_layers, capacity) -> int:
+    return int(load().pipelive_patch_max_blocks(kv.handle, int(n_layers), int(capacity)))
+
+
+def pipelive_kv_read_state(kv: "KVRegion") -> KVState:
+    st = KVState()
+    _check(load().pipelive_kv_read_state(kv.handle, C.byref(st), _stream()))
+    return st
+
+
+def pipelive_kv_clear_status(kv: "KVRegion"):
+    return _check(load().pipelive_kv_clear_status(kv.handle, _stream()))
+
+
+def pipelive_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer, block_bytes_per_layer) -> int:
+    return int(load().pipelive_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer,
+                                          block_bytes_per_layer))
+
+
+# ---- device memory plumbing ------------------------------------------------------
+
+class KVRegion:
+    """Torch allocations + library handle of one KV region on the current device.
+
+    Physical blocks are spread over ``arenas`` separate allocations per layer
+    group (block ``b`` in arena ``b % arenas``) so that no address is
+    ``base + id * stride``.  ``backed_blocks`` limits how many ids get real
+    memory (the rest of the block list is null and must not be used)."""
+
+    def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
+                 capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda"):
+        L = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("pipelive needs a GPU: no CPU fallback exists")
+        self.L_, self.Hq, self.Hkv, self.D, self.bs = num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens
+        self.stack_k = stack_k
+        self.capacity = int(capacity_blocks if capacity_blocks is not None else num_blocks)
+        self.blk_elems = 2 * num_kv_heads * block_tokens * head_dim
+        self.blk_bytes = 2 * self.blk_elems
+        self.groups = (num_layers + stack_k - 1) // stack_k
+        self.device = torch.device(device)
+        phys = self.blk_elems * stack_k
+        self._n_ar = n_ar = max(1, min(arenas, self.capacity))
+        self.arenas = []
+        bl = torch.zeros((self.groups, self.capacity), dtype=torch.int64)
+        for g in range(self.groups):
+            for a in range(n_ar):
+                cnt = len(range(a, self.capacity, n_ar))
+                t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
+                if fill_bits is not None:
+                    t.fill_(fill_bits - 65536 if fill_bits >= 32768 else fill_bits)
+                self.arenas.append(t)
+                bl[g, a::n_ar] = t.data_ptr() + torch.arange(cnt, dtype=torch.int64) * (phys * 2)
+        self.block_list = bl.to(self.device)
+        nb = L.pipelive_bitmap_bytes(self.capacity)
+        self.live = torch.zeros(nb, dtype=torch.uint8, device=self.device)
+        self.dirty = torch.zeros(nb, dtype=torch.uint8, device=self.device)
+        self.state = torch.zeros(L.pipelive_kv_state_bytes(self.capacity), dtype=torch.uint8,
+                                 device=self.device)
+        d = KVDesc(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, stack_k, 0,
+                   LAYOUT_D8, int(num_blocks), self.capacity, self.block_list.data_ptr(),
+                   self.live.data_ptr(), self.dirty.data_ptr(), self.state.data_ptr())
+        h = C.c_void_p()
+        torch.cuda.synchronize()
+        _check(L.pipelive_kv_create(C.byref(d), C.byref(h)))
+        self.handle = h
+        self._ws = {}
+
+    def __del__(self):
+        try:
+            if getattr(self, "handle", None):
+                load().pipelive_kv_destroy(self.handle)
+                self.handle = None
+        except Exception:
+            pass
+
+    @property
+    def num_blocks(self) -> int:
+        return int(load().pipelive_kv_num_blocks(self.handle))
+
+    def block(self, layer: int, block_id: int) -> torch.Tensor:
+        """int16 view [blk_elems] of (layer, block) in device memory."""
+        b = int(block_id)
+        t = self.arenas[(layer // self.stack_k) * self._n_ar + b % self._n_ar]
+        o = (layer % self.stack_k) * self.blk_elems
+        return t[b // self._n_ar, o:o + self.blk_elems]
+
+    def write_blocks(self, layer: int, block_ids, data: torch.Tensor) -> None:
+        """data: int16 [n][blk_elems] on the device -> blocks ``block_ids`` of ``layer``."""
+        ids = torch.as_tensor(block_ids, dtype=torch.int64)
+        o = (layer % self.stack_k) * self.blk_elems
+        for a in range(self._n_ar):
+            sel = (ids % self._n_ar) == a
+            if sel.any():
+                t = self.arenas[(layer // self.stack_k) * self._n_ar + a]
+                rows = (ids[sel] // self._n_ar).to(self.device)
+                t[rows, o:o + self.blk_elems] = data[sel.to(data.device)]
+
+    def read_blocks(self, layer: int, block_ids) -> torch.Tensor:
+        ids = torch.as_tensor(block_ids, dtype=torch.int64)
+        out = torch.empty((len(ids), self.blk_elems), dtype=torch.int16, device=self.device)
+        o = (layer % self.stack_k) * self.blk_elems
+        for a in range(self._n_ar):
+            sel = (ids % self._n_ar) == a
+            if sel.any():
+                t = self.arenas[(layer // self.stack_k) * self._n_ar + a]
+                rows = (ids[sel] // self._n_ar).to(self.device)
+                out[sel.to(self.device)] = t[rows, o:o + self.blk_elems]
+        return out
+
+    def set_live(self, ids) -> None:
+        import numpy as np
+        bm = np.zeros(self.live.numel(), dtype=np.uint8)
+        ids = np.asarray(ids, dtype=np.int64)
+        np.bitwise_or.at(bm, ids >> 3, (1 << (ids & 7)).astype(np.uint8))
+        self.live.copy_(torch.from_numpy(bm))
+
+    def attn_workspace(self, num_seqs, max_ctx, split_tokens=0) -> torch.Tensor:
+        n = load().pipelive_paged_attn_workspace_bytes(self.handle, int(num_seqs), int(max_ctx),
+                                                       int(split_tokens))
+        if n == 0:
+            raise PipeliveError(E_INVAL)
+        key = ("attn", n)
+        if key not in self._ws:
+            self._ws = {k: v for k, v in self._ws.items() if k[0] != "attn"}
+            self._ws[key] = torch.empty(n, dtype=torch.uint8, device=self.device)
+        return self._ws[key]
+
+    def resize_workspace(self) -> torch.Tensor:
+        n = load().pipelive_kv_resize_workspace_bytes(self.handle)
+        key = ("resize", n)
+        if key not in self._ws:
+            self._ws[key] = torch.empty(n, dtype=torch.uint8, device=self.device)
+        return self._ws[key]

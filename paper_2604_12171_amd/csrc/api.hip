@@ -1,0 +1,357 @@
+// Host side of the C ABI: argument validation, launch heuristics, and the one
+// synchronisation that ResizeKV needs for its feasibility verdict.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "internal.h"
+
+using namespace pipelive;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int32_t hip_fail(hipError_t e) {
+  snprintf(g_hip_err, sizeof g_hip_err, "%s", hipGetErrorString(e));
+  return PIPELIVE_E_HIP;
+}
+#define HIP_TRY(expr)                          \
+  do {                                         \
+    hipError_t e_ = (expr);                    \
+    if (e_ != hipSuccess) return hip_fail(e_); \
+  } while (0)
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int g_cu_count = 0;
+
+}  // namespace
+
+namespace pipelive {
+int device_cu_count() {
+  if (g_cu_count == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      g_cu_count = n;
+    else
+      g_cu_count = 256;
+  }
+  return g_cu_count;
+}
+}  // namespace pipelive
+
+extern "C" {
+
+size_t pipelive_bitmap_bytes(int64_t capacity_blocks) {
+  return capacity_blocks <= 0 ? 8 : (size_t)((capacity_blocks + 63) / 64 * 8);
+}
+
+size_t pipelive_kv_state_bytes(int64_t capacity_blocks) {
+  return kSnapOffset + round_up(pipelive_bitmap_bytes(capacity_blocks), 256);
+}
+
+int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
+  if (!d || !out) return PIPELIVE_E_INVAL;
+  *out = nullptr;
+  if (d->num_layers <= 0 || d->num_kv_heads <= 0 || d->num_q_heads <= 0) return PIPELIVE_E_INVAL;
+  if (d->num_q_heads % d->num_kv_heads) return PIPELIVE_E_INVAL;
+  if (d->num_q_heads / d->num_kv_heads > 16) return PIPELIVE_E_INVAL;
+  if (d->head_dim != 64 && d->head_dim != 128) return PIPELIVE_E_INVAL;
+  if (d->block_tokens != 16 && d->block_tokens != 32) return PIPELIVE_E_INVAL;
+  if (d->stack_k < 1 || d->dtype != PIPELIVE_DTYPE_BF16) return PIPELIVE_E_INVAL;
+  if (d->in_block_layout != PIPELIVE_LAYOUT_D8) return PIPELIVE_E_INVAL;
+  if (d->num_blocks < 0 || d->capacity_blocks < d->num_blocks) return PIPELIVE_E_INVAL;
+  if (d->capacity_blocks >= (1ll << 31)) return PIPELIVE_E_INVAL;
+  if (!d->block_list || !d->live_bitmap || !d->dirty_bitmap || !d->dev_state)
+    return PIPELIVE_E_INVAL;
+  if (!aligned(d->live_bitmap, 8) || !aligned(d->dirty_bitmap, 8) || !aligned(d->dev_state, 256) ||
+      !aligned(d->block_list, 8))
+    return PIPELIVE_E_INVAL;
+  pipelive_kv *kv = new (std::nothrow) pipelive_kv;
+  if (!kv) return PIPELIVE_E_NOSPACE;
+  kv->d = *d;
+  kv->groups = (d->num_layers + d->stack_k - 1) / d->stack_k;
+  kv->blk_bytes = (uint64_t)2 * d->num_kv_heads * d->block_tokens * d->head_dim * 2;
+  kv->phys_bytes = kv->blk_bytes * (uint64_t)d->stack_k;
+  kv->pinned = nullptr;
+  hipError_t e = hipHostMalloc((void **)&kv->pinned, sizeof(HostPinned), hipHostMallocDefault);
+  if (e != hipSuccess) {
+    delete kv;
+    return hip_fail(e);
+  }
+  memset(kv->pinned, 0, sizeof(HostPinned));
+  *out = kv;
+  return PIPELIVE_OK;
+}
+
+void pipelive_kv_destroy(pipelive_kv_t *kv) {
+  if (!kv) return;
+  if (kv->pinned) (void)hipHostFree(kv->pinned);
+  delete kv;
+}
+
+int64_t pipelive_kv_num_blocks(const pipelive_kv_t *kv) { return kv ? kv->d.num_blocks : -1; }
+
+/* ------------------------------------------------------------ attention */
+
+static int32_t max_split_tokens(const pipelive_kv_t *kv) { return 64 * kv->d.block_tokens; }
+
+int32_t pipelive_paged_attn_pick_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx) {
+  if (!kv || num_seqs <= 0 || max_ctx <= 0) return 128;
+  // largest split that still gives every CU about eight workgroups
+  const int64_t want = (int64_t)device_cu_count() * 8;
+  int32_t st = max_split_tokens(kv);
+  if (st > 1024) st = 1024;
+  while (st > 128) {
+    const int64_t wgs = (int64_t)num_seqs * kv->d.num_kv_heads * ((max_ctx + st - 1) / st);
+    if (wgs >= want) break;
+    st >>= 1;
+  }
+  return st;
+}
+
+static int32_t resolve_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx,
+                             int32_t split_tokens) {
+  if (split_tokens == 0) return pipelive_paged_attn_pick_split(kv, num_seqs, max_ctx);
+  if (split_tokens < 0 || split_tokens % 64 || split_tokens > max_split_tokens(kv)) return -1;
+  return split_tokens;
+}
+
+size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
+                                           int32_t max_ctx, int32_t split_tokens) {
+  if (!kv || num_seqs <= 0 || max_ctx <= 0) return 256;
+  const int32_t st = resolve_split(kv, num_seqs, max_ctx, split_tokens);
+  if (st < 0) return 0;
+  const size_t splits = (size_t)((max_ctx + st - 1) / st);
+  const size_t rows = (size_t)num_seqs * kv->d.num_q_heads * splits;
+  return round_up(rows * kv->d.head_dim * 4, 256) + round_up(rows * 8, 256);
+}
+
+int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                   int32_t out_dtype, const int32_t *block_table,
+                                   int32_t table_stride, const int32_t *ctx_lens, int32_t num_seqs,
+                                   int32_t max_ctx, float scale, int32_t split_tokens,
+                                   void *workspace, size_t workspace_bytes, void *stream) {
+  if (!kv || !q || !out || !block_table || !ctx_lens) return PIPELIVE_E_INVAL;
+  if (layer < 0 || layer >= kv->d.num_layers) return PIPELIVE_E_RANGE;
+  if (num_seqs < 0 || table_stride <= 0) return PIPELIVE_E_INVAL;
+  if (out_dtype != PIPELIVE_OUT_F32 && out_dtype != PIPELIVE_OUT_BF16) return PIPELIVE_E_INVAL;
+  if (!aligned(q, 16) || !aligned(out, 4)) return PIPELIVE_E_INVAL;
+  if (num_seqs == 0) return PIPELIVE_OK;
+  const int64_t table_cap = (int64_t)table_stride * kv->d.block_tokens;
+  if (max_ctx <= 0 || max_ctx > table_cap) max_ctx = (int32_t)(table_cap > 0x7FFFFFF0 ? 0x7FFFFFF0 : table_cap);
+  const int32_t st = resolve_split(kv, num_seqs, max_ctx, split_tokens);
+  if (st < 0) return PIPELIVE_E_INVAL;
+  const size_t need = pipelive_paged_attn_workspace_bytes(kv, num_seqs, max_ctx, st);
+  if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return PIPELIVE_E_NOSPACE;
+
+  AttnParams p;
+  p.block_list = kv->d.block_list + (int64_t)(layer / kv->d.stack_k) * kv->d.capacity_blocks;
+  p.layer_off = (uint32_t)((layer % kv->d.stack_k) * kv->blk_bytes);
+  p.q = (const uint16_t *)q;
+  p.out = out;
+  p.out_dtype = out_dtype;
+  p.table = block_table;
+  p.table_stride = table_stride;
+  p.ctx = ctx_lens;
+  p.num_seqs = num_seqs;
+  p.max_ctx = max_ctx;
+  p.Hq = kv->d.num_q_heads;
+  p.Hkv = kv->d.num_kv_heads;
+  p.G = p.Hq / p.Hkv;
+  const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)kv->d.head_dim);
+  p.scale_log2 = sc * 1.4426950408889634f;
+  p.split_tokens = st;
+  p.max_splits = (max_ctx + st - 1) / st;
+  const size_t rows = (size_t)num_seqs * p.Hq * p.max_splits;
+  p.ws_o = (float *)workspace;
+  p.ws_ml = (float *)((char *)workspace + round_up(rows * kv->d.head_dim * 4, 256));
+  p.num_blocks = kv->d.num_blocks;
+  p.status = &dev_state(kv)->status;
+  if (p.max_splits > 65535 || p.Hkv > 65535 || num_seqs > 65535) return PIPELIVE_E_INVAL;
+  HIP_TRY(launch_attn_decode(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
+/* --------------------------------------------------------------- resize */
+
+size_t pipelive_kv_resize_workspace_bytes(const pipelive_kv_t *kv) {
+  if (!kv) return 0;
+  const size_t cap = (size_t)(kv->d.capacity_blocks > 0 ? kv->d.capacity_blocks : 1);
+  return 256 + 3 * round_up(cap * 4, 256);
+}
+
+int64_t pipelive_max_blocks(double mem_bytes, double util, int64_t layers,
+                            double weight_bytes_per_layer, double block_bytes_per_layer) {
+  if (layers <= 0 || block_bytes_per_layer <= 0) return 0;
+  const double v = (mem_bytes * util - (double)layers * weight_bytes_per_layer) /
+                   ((double)layers * block_bytes_per_layer);
+  return v < 0 ? 0 : (int64_t)floor(v);
+}
+
+int32_t pipelive_kv_resize(pipelive_kv_t *kv, int64_t new_num_blocks, int32_t *const *block_tables,
+                           const int32_t *table_rows, const int32_t *table_strides,
+                           const int32_t *const *table_used, int32_t num_tables,
+                           int32_t *remap_out, pipelive_resize_result_t *result, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+  if (!kv || new_num_blocks < 0 || num_tables < 0 || num_tables > PIPELIVE_MAX_TABLES)
+    return PIPELIVE_E_INVAL;
+  if (num_tables > 0 && (!block_tables || !table_rows || !table_strides || !table_used))
+    return PIPELIVE_E_INVAL;
+  TableRef tabs[PIPELIVE_MAX_TABLES];
+  for (int t = 0; t < num_tables; ++t) {
+    if (!block_tables[t] || !table_used[t] || table_rows[t] < 0 || table_strides[t] <= 0)
+      return PIPELIVE_E_INVAL;
+    tabs[t].table = block_tables[t];
+    tabs[t].used = table_used[t];
+    tabs[t].rows = table_rows[t];
+    tabs[t].stride = table_strides[t];
+  }
+  if (!workspace || !aligned(workspace, 256) ||
+      workspace_bytes < pipelive_kv_resize_workspace_bytes(kv))
+    return PIPELIVE_E_NOSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t B = kv->d.num_blocks;
+  const size_t cap = (size_t)(kv->d.capacity_blocks > 0 ? kv->d.capacity_blocks : 1);
+  ResizePlanOut *plan = (ResizePlanOut *)workspace;
+  int32_t *move_src = (int32_t *)((char *)workspace + 256);
+  int32_t *move_dst = (int32_t *)((char *)move_src + round_up(cap * 4, 256));
+  int32_t *remap = remap_out ? remap_out : (int32_t *)((char *)move_dst + round_up(cap * 4, 256));
+
+  pipelive_resize_result_t res;
+  memset(&res, 0, sizeof res);
+  res.old_num_blocks = B;
+  res.new_num_blocks = B;
+  int32_t rc = PIPELIVE_OK;
+
+  HIP_TRY(launch_resize_plan(kv, B, new_num_blocks, plan, move_src, move_dst, st));
+  for (int t = 0; t < num_tables; ++t) HIP_TRY(launch_table_check(kv, B, tabs[t], plan, st));
+  HIP_TRY(hipMemcpyAsync(kv->pinned->plan, plan, sizeof(ResizePlanOut), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  const int64_t n_live = kv->pinned->plan[0], n_moved = kv->pinned->plan[1];
+  const bool any_dirty = kv->pinned->plan[2] != 0, bad_table = kv->pinned->plan[3] != 0;
+  res.n_live = n_live;
+  if (new_num_blocks > kv->d.capacity_blocks) rc = PIPELIVE_E_NOSPACE;
+  else if (any_dirty) rc = PIPELIVE_E_BUSY;
+  else if (n_live > new_num_blocks) rc = PIPELIVE_E_INFEASIBLE;
+  else if (bad_table) rc = PIPELIVE_E_RANGE;
+
+  if (rc == PIPELIVE_OK) {
+    if (new_num_blocks < B) {
+      HIP_TRY(launch_resize_commit(kv, B, new_num_blocks, n_moved, move_src, move_dst, remap, tabs,
+                                   num_tables, st));
+      res.n_moved = n_moved;
+    } else {
+      HIP_TRY(launch_grow(kv, B, new_num_blocks, remap, st));
+    }
+    kv->d.num_blocks = new_num_blocks;
+    res.new_num_blocks = new_num_blocks;
+  }
+  res.status = rc;
+  if (result) *result = res;
+  return rc;
+}
+
+/* ---------------------------------------------------------------- patch */
+
+int32_t pipelive_kv_mark_dirty(pipelive_kv_t *kv, const int32_t *block_ids, int32_t n,
+                               int64_t n_tokens, void *stream) {
+  if (!kv || n < 0 || n_tokens < 0 || (n > 0 && !block_ids)) return PIPELIVE_E_INVAL;
+  if (n == 0 && n_tokens == 0) return PIPELIVE_OK;
+  HIP_TRY(launch_mark(kv, block_ids, n, n_tokens, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
+int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, size_t capacity) {
+  if (!kv || n_layers <= 0 || capacity < 64 + 256) return 0;
+  const uint64_t per = 4 + (uint64_t)n_layers * kv->blk_bytes;
+  uint64_t mb = (capacity - 64 - 256) / per;
+  if (mb > (uint64_t)kv->d.num_blocks) mb = (uint64_t)kv->d.num_blocks;
+  return (int64_t)mb;
+}
+
+static int32_t fill_layers(const pipelive_kv_t *kv, const int32_t *layers, int32_t n, LayerList *ll) {
+  if (!layers || n <= 0 || n > PIPELIVE_MAX_PATCH_LAYERS) return PIPELIVE_E_INVAL;
+  ll->n = n;
+  for (int i = 0; i < n; ++i) {
+    if (layers[i] < 0 || layers[i] >= kv->d.num_layers) return PIPELIVE_E_RANGE;
+    ll->layer[i] = layers[i];
+  }
+  for (int i = n; i < PIPELIVE_MAX_PATCH_LAYERS; ++i) ll->layer[i] = 0;
+  return PIPELIVE_OK;
+}
+
+int32_t pipelive_kv_patch_collect(pipelive_kv_t *src, const int32_t *layers, int32_t n_layers,
+                                  void *patch_buf, size_t patch_capacity_bytes,
+                                  pipelive_patch_hdr_t *hdr_host_copy, void *stream) {
+  if (!src || !patch_buf || !aligned(patch_buf, 256)) return PIPELIVE_E_INVAL;
+  LayerList ll;
+  int32_t rc = fill_layers(src, layers, n_layers, &ll);
+  if (rc != PIPELIVE_OK) return rc;
+  const int64_t mb = pipelive_patch_max_blocks(src, n_layers, patch_capacity_bytes);
+  if (mb <= 0) return PIPELIVE_E_NOSPACE;
+  const uint64_t payload_offset = round_up(64 + 4 * (uint64_t)mb, 256);
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(launch_collect(src, ll, (uint8_t *)patch_buf, (uint32_t)mb, payload_offset, st));
+  if (hdr_host_copy)
+    HIP_TRY(hipMemcpyAsync(hdr_host_copy, patch_buf, sizeof(pipelive_patch_hdr_t),
+                           hipMemcpyDeviceToHost, st));
+  return PIPELIVE_OK;
+}
+
+int32_t pipelive_kv_patch_apply(pipelive_kv_t *dst, const int32_t *dst_layers, int32_t n_layers,
+                                const void *patch_buf, const int32_t *dst_block_map, void *stream) {
+  if (!dst || !patch_buf || !aligned(patch_buf, 256)) return PIPELIVE_E_INVAL;
+  LayerList ll;
+  int32_t rc = fill_layers(dst, dst_layers, n_layers, &ll);
+  if (rc != PIPELIVE_OK) return rc;
+  HIP_TRY(launch_apply(dst, ll, (const uint8_t *)patch_buf, dst_block_map, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
+int32_t pipelive_kv_read_state(pipelive_kv_t *kv, pipelive_kv_state_t *out, void *stream) {
+  if (!kv || !out) return PIPELIVE_E_INVAL;
+  hipStream_t st = (hipStream_t)stream;
+  HIP_TRY(hipMemcpyAsync(&kv->pinned->state, dev_state(kv), sizeof(DevState), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  out->n_acc = kv->pinned->state.n_acc;
+  out->t_applied = kv->pinned->state.t_applied;
+  out->status = kv->pinned->state.status;
+  out->reserved = 0;
+  return PIPELIVE_OK;
+}
+
+int32_t pipelive_kv_clear_status(pipelive_kv_t *kv, void *stream) {
+  if (!kv) return PIPELIVE_E_INVAL;
+  HIP_TRY(launch_clear_status(kv, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
+const char *pipelive_strerror(int32_t code) {
+  switch (code) {
+    case PIPELIVE_OK: return "ok";
+    case PIPELIVE_E_INVAL: return "invalid argument";
+    case PIPELIVE_E_INFEASIBLE: return "infeasible: more live blocks than the requested pool size";
+    case PIPELIVE_E_NOSPACE: return "no space: capacity, workspace or patch buffer too small";
+    case PIPELIVE_E_BUSY: return "busy: dirty blocks pending";
+    case PIPELIVE_E_RANGE: return "block id or layer out of range";
+    case PIPELIVE_E_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+const char *pipelive_last_hip_error(void) { return g_hip_err; }
+
+int32_t pipelive_device_ok(void) {
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+  return strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Internal declarations shared by the host API and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pipelive.h"
+
+namespace pipelive {
+
+// Per-region device state (at desc.dev_state).  The drain snapshot words
+// follow at byte offset kSnapOffset.
+struct DevState {
+  unsigned long long n_acc;      // tokens marked since the last complete drain
+  unsigned long long t_applied;  // T_applied
+  int32_t status;                // sticky: first PIPELIVE_E_* seen on the device
+  int32_t pad_[11];
+};
+static_assert(sizeof(DevState) == 64, "DevState layout");
+constexpr size_t kSnapOffset = 256;
+
+struct HostPinned {  // small pinned mailbox per handle
+  int64_t plan[8];
+  DevState state;
+};
+
+}  // namespace pipelive
+
+struct pipelive_kv {
+  pipelive_kv_desc_t d;
+  int64_t groups;
+  uint64_t blk_bytes;   // one (layer, block)
+  uint64_t phys_bytes;  // one physical block = stack_k * blk_bytes
+  pipelive::HostPinned *pinned;
+};
+
+namespace pipelive {
+
+inline DevState *dev_state(const pipelive_kv *kv) { return (DevState *)kv->d.dev_state; }
+inline unsigned long long *snap_words(const pipelive_kv *kv) {
+  return (unsigned long long *)((char *)kv->d.dev_state + kSnapOffset);
+}
+
+// ---- attention
+struct AttnParams {
+  const uint64_t *block_list;  // this layer's group row
+  uint32_t layer_off;          // byte offset of the layer inside a physical block
+  const uint16_t *q;
+  void *out;
+  int32_t out_dtype;
+  const int32_t *table;
+  int32_t table_stride;
+  const int32_t *ctx;
+  int32_t num_seqs, max_ctx;
+  int32_t Hq, Hkv, G;
+  float scale_log2;  // scale * log2(e)
+  int32_t split_tokens, max_splits;
+  float *ws_o;   // [S][Hq][max_splits][D]
+  float *ws_ml;  // [S][Hq][max_splits][2]
+  int64_t num_blocks;
+  int32_t *status;
+};
+hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st);
+
+// ---- resize
+struct TableRef {
+  int32_t *table;
+  const int32_t *used;
+  int32_t rows, stride;
+};
+struct ResizePlanOut {  // in the workspace
+  long long n_live, n_moved, any_dirty, bad_table;
+};
+hipError_t launch_resize_plan(const pipelive_kv *kv, int64_t B, int64_t B_new, ResizePlanOut *plan,
+                              int32_t *move_src, int32_t *move_dst, hipStream_t st);
+hipError_t launch_table_check(const pipelive_kv *kv, int64_t B, const TableRef &t,
+                              ResizePlanOut *plan, hipStream_t st);
+hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new, int64_t n_moved,
+                                const int32_t *move_src, const int32_t *move_dst, int32_t *remap,
+                                const TableRef *tables, int n_tables, hipStream_t st);
+hipError_t launch_grow(const pipelive_kv *kv, int64_t B, int64_t B_new, int32_t *remap,
+                       hipStream_t st);
+
+// ---- patch
+struct LayerList {
+  int32_t n;
+  int32_t layer[PIPELIVE_MAX_PATCH_LAYERS];
+};
+hipError_t launch_mark(const pipelive_kv *kv, const int32_t *ids, int32_t n, int64_t n_tokens,
+                       hipStream_t st);
+hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
+                          uint32_t max_blocks, uint64_t payload_offset, hipStream_t st);
+hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,
+                        const int32_t *dst_map, hipStream_t st);
+hipError_t launch_clear_status(const pipelive_kv *kv, hipStream_t st);
+
+int device_cu_count();
+
+}  // namespace pipelive

@@ -1,0 +1,35 @@
+// Block-copy primitive shared by resize (move), patch collect (gather) and
+// patch apply (scatter): a workgroup of 256 lanes streams one chunk with
+// 16-byte loads and stores, several loads in flight per lane before the first
+// store.  Pure HBM traffic: every payload byte is read once and written once.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pipelive {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kCopyThreads = 256;
+constexpr int kCopyUnroll = 4;
+constexpr uint32_t kCopyChunk = kCopyThreads * 16 * kCopyUnroll;  // 16 KiB per workgroup pass
+
+// copy `bytes` (a multiple of 16) from src to dst, both 16-B aligned, by one workgroup
+__device__ __forceinline__ void wg_copy(char *__restrict__ dst, const char *__restrict__ src,
+                                        uint32_t bytes) {
+  const uint32_t tid = threadIdx.x;
+  uint32_t off = 0;
+  for (; off + kCopyChunk <= bytes; off += kCopyChunk) {
+    u32x4 v[kCopyUnroll];
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u)
+      v[u] = __builtin_nontemporal_load((const u32x4 *)(src + off + (u * kCopyThreads + tid) * 16));
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u)
+      __builtin_nontemporal_store(v[u], (u32x4 *)(dst + off + (u * kCopyThreads + tid) * 16));
+  }
+  for (uint32_t o = off + tid * 16; o < bytes; o += kCopyThreads * 16)
+    *(u32x4 *)(dst + o) = *(const u32x4 *)(src + o);
+}
+
+}  // namespace pipelive
