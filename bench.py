@@ -1,0 +1,301 @@
+#!/usr/bin/env python3
+"""Benchmark of the PipeLive hot path on one MI355X.
+
+Workload (default): the Llama-3-8B-shaped pipeline stage - 16 layers, 32 query
+/ 8 KV heads, head_dim 128, block 16 tokens, bf16, 64 sequences with context
+lengths uniform in [512, 4096], block pool sized to 85 % of the HBM left after
+the stage's fp16 weights.  One *step* is one pass of the whole hot path on that
+batch:
+
+  1. decode attention over all layers (one launch per layer, own q per layer),
+  2. one patch cycle: mark every sequence's last block dirty, collect
+     (drain + gather) the dirty blocks of the migrating layers into the patch
+     buffer, apply (scatter) them into the target region,
+  3. ResizeKV: shrink the pool by 20 % (plan, move, remap) - followed by an
+     untimed-in-bytes restore (grow back + reset of table and live bitmap) so
+     that every step performs the same moves.
+
+`value` is the algorithmic bytes of the whole step divided by the step time.
+The per-phase figures (HIP events on the launch stream) and the roofline of the
+dominant kernel (decode attention) are reported beside it, and the CPU oracle is
+timed on the host cores on a bounded sample of the same workload.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="stage8b", help="workload name (see pipelive_inputs.CONFIGS)")
+    ap.add_argument("--split-tokens", type=int, default=0)
+    ap.add_argument("--mig-layers", type=int, default=4, help="layers carried by each patch")
+    ap.add_argument("--pool-blocks", type=int, default=0, help="override the pool size (blocks per layer)")
+    ap.add_argument("--shrink", type=float, default=0.20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers in the CPU oracle sample")
+    ap.add_argument("--decode-only", action="store_true", help="profiling aid: steps run phase 1 only")
+    return ap.parse_args()
+
+
+def stage_weight_bytes(cfg) -> int:
+    """fp16 weights of the stage's layers (Llama shapes: hidden = Hq*D, 3.5x MLP)."""
+    hidden = cfg.num_q_heads * cfg.head_dim
+    kvdim = cfg.num_kv_heads * cfg.head_dim
+    inter = {4096: 14336, 8192: 28672}.get(hidden, 4 * hidden)
+    per_layer = hidden * hidden * 2 + 2 * hidden * kvdim + 3 * hidden * inter
+    return 2 * per_layer * cfg.num_layers
+
+
+def read_traffic(kernel_tag: str):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", f"{kernel_tag}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+            f"--gpus {args.gpus} is not supported.")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import pipelive_inputs as pin
+    from pipelive_inputs.device_fill import fill_live_blocks
+    import paper_2604_12171_amd as P
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the hot path has no CPU fallback.")
+        sys.exit(3)
+    torch.cuda.set_device(0)
+    lib = P.load()
+    dev_name = torch.cuda.get_device_name(0)
+    cfg = pin.CONFIGS[args.config]
+    seed = pin.MASTER_SEED
+    L, S = cfg.num_layers, cfg.num_seqs
+
+    # ---------------- pool sizing: 85 % of the HBM left after the stage weights
+    t_setup = time.time()
+    weights = torch.empty(stage_weight_bytes(cfg), dtype=torch.uint8, device="cuda")
+    free, total = torch.cuda.mem_get_info()
+    ctx = pin.draw_ctx_lens(cfg, seed)
+    n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
+    B = args.pool_blocks or int(0.85 * free // (L * cfg.blk_bytes))
+    B = max(B, int(math.ceil(n_live * 1.3)))
+    region = None
+    while region is None:
+        try:
+            region = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
+                                B, arenas=4)
+        except torch.OutOfMemoryError:
+            log(f"pool of {B} blocks/layer does not fit; halving")
+            torch.cuda.empty_cache()
+            B //= 2
+    batch = pin.draw_batch(cfg, seed, num_blocks=B)
+    log(f"[setup] {dev_name}: pool {B} blocks/layer x {L} layers = {B * L * cfg.blk_bytes / 2**30:.1f} GiB "
+        f"(free after weights {free / 2**30:.1f} GiB), live {n_live} blocks/layer, "
+        f"tokens {batch.total_tokens}")
+    fill_live_blocks(region, cfg, batch, seed, B, poison_tail=True)
+    torch.cuda.synchronize()
+    log(f"[setup] pool filled in {time.time() - t_setup:.1f}s")
+
+    table_d = torch.from_numpy(batch.table).cuda()
+    table_saved = table_d.clone()
+    ctx_d = torch.from_numpy(batch.ctx_lens).cuda()
+    used_d = torch.from_numpy(batch.used).cuda()
+    live_saved = region.live.clone()
+    max_ctx = int(batch.ctx_lens.max())
+    split = args.split_tokens or lib.pipelive_paged_attn_pick_split(region.handle, S, max_ctx)
+    ws = region.attn_workspace(S, max_ctx, split)
+    qs = [torch.from_numpy(pin.q_bits(cfg, seed, l).view(np.int16)).cuda().view(torch.bfloat16)
+          for l in range(L)]
+    outs = [torch.empty((S, cfg.num_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+            for _ in range(L)]
+
+    # migration target: a compact region reached through a block map
+    Lm = min(args.mig_layers, L)
+    mig_layers = list(range(L - Lm, L))
+    target = P.KVRegion(Lm, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
+                        n_live, arenas=2)
+    dst_map = torch.full((B,), -1, dtype=torch.int32)
+    dst_map[torch.from_numpy(batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
+    dst_map = dst_map.cuda()
+    last_ids = torch.from_numpy(pin.last_block_ids(batch).astype(np.int32)).cuda()
+    n_dirty = int(last_ids.numel())
+    patch_cap = 64 + 256 + n_dirty * (4 + Lm * cfg.blk_bytes) + 4096
+    patch = torch.empty(patch_cap, dtype=torch.uint8, device="cuda")
+    B_new = int(B * (1.0 - args.shrink))
+    n_moved_expect = int((batch.live_ids >= B_new).sum())
+    rws = region.resize_workspace()
+
+    # ---------------- algorithmic bytes
+    kv_bytes_layer = batch.total_tokens * cfg.token_bytes
+    q_bytes = S * cfg.num_q_heads * cfg.head_dim * 2
+    out_bytes = S * cfg.num_q_heads * cfg.head_dim * 4
+    tab_bytes = 4 * int(batch.used.sum())
+    attn_bytes_layer = kv_bytes_layer + q_bytes + out_bytes + tab_bytes
+    decode_bytes = attn_bytes_layer * L
+    patch_payload = n_dirty * Lm * cfg.blk_bytes
+    collect_bytes = 2 * patch_payload + 2 * (B // 8)
+    apply_bytes = 2 * patch_payload
+    resize_bytes = 2 * n_moved_expect * L * cfg.blk_bytes
+    step_bytes = decode_bytes if args.decode_only else decode_bytes + collect_bytes + apply_bytes + resize_bytes
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def one_step(events=None):
+        if events:
+            events[0].record()
+        for l in range(L):
+            P.pipelive_paged_attn_decode(region, l, qs[l], outs[l], table_d, ctx_d, max_ctx=max_ctx,
+                                         split_tokens=split, workspace=ws)
+        if events:
+            events[1].record()
+        if args.decode_only:
+            return
+        P.pipelive_kv_mark_dirty(region, last_ids, S)
+        P.pipelive_kv_patch_collect(region, mig_layers, patch)
+        if events:
+            events[2].record()
+        P.pipelive_kv_patch_apply(target, list(range(Lm)), patch, dst_block_map=dst_map)
+        if events:
+            events[3].record()
+        rc, res = P.pipelive_kv_resize(region, B_new, [table_d], [used_d], workspace=rws)
+        if rc != P.OK or res.n_moved != n_moved_expect:
+            raise RuntimeError(f"resize failed: rc={rc} moved={res.n_moved} expected={n_moved_expect}")
+        if events:
+            events[4].record()
+        # restore (not counted in bytes): grow back, put table and live bitmap back
+        rc, _ = P.pipelive_kv_resize(region, B, [], [], workspace=rws)
+        if rc != P.OK:
+            raise RuntimeError(f"grow failed: {rc}")
+        table_d.copy_(table_saved)
+        region.live.copy_(live_saved)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    all_events = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(all_events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    def phase_ms(a, b):
+        v = sorted(e[a].elapsed_time(e[b]) for e in all_events)
+        return sum(v) / len(v), v[len(v) // 2], v[0]
+
+    dec_avg, dec_med, dec_min = phase_ms(0, 1)
+    result = {
+        "metric": "hot-path HBM GB/s per step (decode paged attention over all layers + KV patch cycle + KV resize)",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {L} layers, {cfg.num_q_heads}q/{cfg.num_kv_heads}kv heads, "
+                               f"D{cfg.head_dim}, block {cfg.block_tokens}, batch {S}, ctx U[{cfg.ctx_lo},{cfg.ctx_hi}]",
+                   "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
+                   "live_blocks_per_layer": n_live, "tokens": batch.total_tokens,
+                   "split_tokens": int(split), "mig_layers": Lm, "device": dev_name,
+                   "decode_only": bool(args.decode_only)},
+        "step_bytes": int(step_bytes),
+        "decode": {"GBps": round(decode_bytes / (dec_avg * 1e-3) / 1e9, 1),
+                   "frac_of_peak": round(decode_bytes / (dec_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                   "ms_avg": round(dec_avg, 4), "ms_median": round(dec_med, 4), "ms_min": round(dec_min, 4),
+                   "bytes": int(decode_bytes)},
+    }
+    launch_us = dec_avg * 1e3 / L
+    result["roofline"] = {
+        "bound": "hbm", "kernel": "attn_decode_kernel<128,16> (+ combine), one launch per layer",
+        "achieved": round(attn_bytes_layer / (launch_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": round(attn_bytes_layer / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+        "traffic": read_traffic(f"attn_decode_{cfg.name}"),
+        "bytes_per_launch": int(attn_bytes_layer), "us_per_launch": round(launch_us, 2),
+    }
+    if not args.decode_only:
+        col_avg, _, col_min = phase_ms(1, 2)
+        app_avg, _, app_min = phase_ms(2, 3)
+        rsz_avg, _, rsz_min = phase_ms(3, 4)
+        result["patch"] = {
+            "dirty_blocks": n_dirty, "payload_bytes": int(patch_payload),
+            "collect_us": round(col_avg * 1e3, 1), "collect_GBps": round(collect_bytes / (col_avg * 1e-3) / 1e9, 1),
+            "apply_us": round(app_avg * 1e3, 1), "apply_GBps": round(apply_bytes / (app_avg * 1e-3) / 1e9, 1)}
+        result["resize"] = {
+            "shrink_to": B_new, "n_moved": n_moved_expect, "bytes": int(resize_bytes),
+            "us": round(rsz_avg * 1e3, 1), "GBps": round(resize_bytes / (rsz_avg * 1e-3) / 1e9, 1),
+            "frac_of_peak": round(resize_bytes / (rsz_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        result["switch_us"] = round((col_avg + app_avg + rsz_avg) * 1e3, 1)
+
+    # ---------------- CPU oracle on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        import oracle
+        ncores = min(16, os.cpu_count() or 1)
+        Lc = max(1, min(L, args.cpu_layers))
+        ids = batch.live_ids
+        compact = np.full(B, -1, dtype=np.int32)
+        compact[ids] = np.arange(len(ids), dtype=np.int32)
+        n_ar = 3
+        host = oracle.HostKV(Lc, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
+                             len(ids), layout=cfg.layout, arenas=n_ar)
+        for l in range(Lc):
+            data = region.read_blocks(l, ids).cpu().numpy().view(np.uint16)   # the inputs, copied back
+            for a in range(n_ar):
+                host.arenas[l * n_ar + a][:] = data[a::n_ar]
+        tab = np.where(batch.table == pin.TABLE_FILL, pin.TABLE_FILL, compact[np.minimum(batch.table, B - 1)])
+        tab = np.ascontiguousarray(tab, dtype=np.int32)
+        tc, err, num, den = 0.0, 0.0, 0.0, 0.0
+        for l in range(Lc):
+            qh = pin.q_bits(cfg, seed, l)
+            tc0 = time.perf_counter()
+            ref = host.attn_decode(l, qh, tab, batch.ctx_lens, nthreads=ncores)
+            tc += time.perf_counter() - tc0
+            got = outs[l].cpu().numpy().astype(np.float64)
+            err = max(err, float(np.abs(got - ref).max()))
+            num += float(((got - ref) ** 2).sum())
+            den += float((ref.astype(np.float64) ** 2).sum())
+        cpu_bytes = Lc * batch.total_tokens * cfg.token_bytes
+        result["cpu_baseline"] = {
+            "value": round(cpu_bytes / tc / 1e9, 4), "unit": "GB/s", "cores": ncores, "kind": "oracle",
+            "sample": f"decode attention of layers 0..{Lc - 1} of {L} (all {S} sequences, all "
+                      f"{cfg.num_q_heads} heads, {Lc * batch.total_tokens} token-layers), {tc:.2f} s wall on "
+                      f"{ncores} threads",
+            "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_rel_l2": math.sqrt(num / den)}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
