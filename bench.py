@@ -134,7 +134,7 @@ def main():
     used_d = torch.from_numpy(batch.used).cuda()
     live_saved = region.live.clone()
     max_ctx = int(batch.ctx_lens.max())
-    split = args.split_tokens or lib.pipelive_paged_attn_pick_split(region.handle, S, max_ctx)
+    split = args.split_tokens
     ws = region.attn_workspace(S, max_ctx, split)
     qs = [torch.from_numpy(pin.q_bits(cfg, seed, l).view(np.int16)).cuda().view(torch.bfloat16)
           for l in range(L)]

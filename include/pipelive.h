@@ -104,18 +104,23 @@ int64_t pipelive_kv_num_blocks(const pipelive_kv_t *kv);
  * the result (they may hold NaN).
  *
  * q            DEVICE bf16 [num_seqs][Hq][D], 16-B aligned
- * out          DEVICE [num_seqs][Hq][D], fp32 (PIPELIVE_OUT_F32) or bf16
+ * out          DEVICE [num_seqs][Hq][D], fp32 (PIPELIVE_OUT_F32) or bf16, 16-B aligned
  * block_table  DEVICE int32 [num_seqs][table_stride] of block ids; only the
  *              first ceil(ctx/bs) entries of a row are read
  * ctx_lens     DEVICE int32 [num_seqs]
  * max_ctx      HOST upper bound on ctx_lens (sizes the launch; sequences
  *              longer than it are truncated to it and flagged E_RANGE)
  * scale        <= 0 selects 1/sqrt(D)
- * split_tokens tokens per workgroup (a multiple of 64); 0 = library
- *              heuristic.  For equal split_tokens the result is bit-identical
- *              whatever the physical placement of the blocks.
+ * split_tokens tokens of (sequence, KV head) work per wavefront, a multiple of
+ *              32; 0 = cut the whole batch into equal shares, one per
+ *              wavefront the device keeps resident (best throughput).  The
+ *              partition depends only on ctx_lens, max_ctx and this value, so
+ *              for equal arguments the result is bit-identical whatever the
+ *              physical placement of the blocks.
  * workspace    DEVICE, >= pipelive_paged_attn_workspace_bytes(...), 256-B
- *              aligned; holds the per-split partial results
+ *              aligned; holds the partial results of (sequence, head) pairs
+ *              that are cut by a share boundary.  Two calls that may run
+ *              concurrently need two workspaces.
  * Asynchronous on `stream`.
  */
 int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
@@ -125,8 +130,6 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
                                    void *workspace, size_t workspace_bytes, void *stream);
 size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
                                            int32_t max_ctx, int32_t split_tokens);
-/* the split size the heuristic would pick for this launch */
-int32_t pipelive_paged_attn_pick_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx);
 
 /* -------------------------------------------------------------------------
  * 2. ResizeKV(B) with compaction (Sec. 4.2 primitive ResizeKV; Alg. 1 phases

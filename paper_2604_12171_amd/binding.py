@@ -27,7 +27,7 @@ PATCH_MAGIC = 0x564B4C50
 EXPORTS = [
     "pipelive_bitmap_bytes", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
     "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_workspace_bytes",
-    "pipelive_paged_attn_pick_split", "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
+    "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
     "pipelive_kv_clear_status", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
@@ -92,8 +92,6 @@ def load(path: str | None = None):
                                              i32, vp, sz, vp]
     L.pipelive_paged_attn_workspace_bytes.restype = sz
     L.pipelive_paged_attn_workspace_bytes.argtypes = [vp, i32, i32, i32]
-    L.pipelive_paged_attn_pick_split.restype = i32
-    L.pipelive_paged_attn_pick_split.argtypes = [vp, i32, i32]
     L.pipelive_kv_resize.restype = i32
     L.pipelive_kv_resize.argtypes = [vp, i64, vp, vp, vp, vp, i32, vp, C.POINTER(ResizeResult), vp,
                                      sz, vp]
@@ -334,7 +332,7 @@ class KVRegion:
         key = ("attn", n)
         if key not in self._ws:
             self._ws = {k: v for k, v in self._ws.items() if k[0] != "attn"}
-            self._ws[key] = torch.empty(n, dtype=torch.uint8, device=self.device)
+            self._ws[key] = torch.zeros(n, dtype=torch.uint8, device=self.device)  # zeroed once
         return self._ws[key]
 
     def resize_workspace(self) -> torch.Tensor:

@@ -2,6 +2,7 @@
 // synchronisation that ResizeKV needs for its feasibility verdict.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -99,37 +100,49 @@ int64_t pipelive_kv_num_blocks(const pipelive_kv_t *kv) { return kv ? kv->d.num_
 
 /* ------------------------------------------------------------ attention */
 
-static int32_t max_split_tokens(const pipelive_kv_t *kv) { return 64 * kv->d.block_tokens; }
+// launch shape: number of waves and share size for a decode call
+struct AttnShape {
+  int32_t num_waves, tiles_per_wave;
+};
 
-int32_t pipelive_paged_attn_pick_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx) {
-  if (!kv || num_seqs <= 0 || max_ctx <= 0) return 128;
-  // largest split that still gives every CU about eight workgroups
-  const int64_t want = (int64_t)device_cu_count() * 8;
-  int32_t st = max_split_tokens(kv);
-  if (st > 1024) st = 1024;
-  while (st > 128) {
-    const int64_t wgs = (int64_t)num_seqs * kv->d.num_kv_heads * ((max_ctx + st - 1) / st);
-    if (wgs >= want) break;
-    st >>= 1;
+static bool attn_shape(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx,
+                       int32_t split_tokens, AttnShape *out) {
+  if (split_tokens < 0 || split_tokens % 32) return false;
+  const int64_t upper = (int64_t)num_seqs * kv->d.num_kv_heads * ((max_ctx + 31) / 32);
+  if (split_tokens == 0) {
+    // equal shares over exactly the waves the device keeps resident
+    int wpc = attn_waves_per_cu(kv->d.head_dim, kv->d.block_tokens);
+    if (const char *e = getenv("PIPELIVE_ATTN_WAVES_PER_CU")) {  // tuning aid
+      const int v = atoi(e);
+      if (v >= 1 && v <= wpc) wpc = v;
+    }
+    const int64_t resident = (int64_t)device_cu_count() * wpc;
+    int64_t nw = upper < resident ? upper : resident;
+    out->num_waves = (int32_t)(nw < 1 ? 1 : nw);
+    out->tiles_per_wave = 0;
+  } else {
+    const int64_t q = split_tokens / 32;
+    const int64_t nw = (upper + q - 1) / q;
+    if (nw > (1ll << 30)) return false;
+    out->num_waves = (int32_t)(nw < 1 ? 1 : nw);
+    out->tiles_per_wave = (int32_t)q;
   }
-  return st;
+  return true;
 }
 
-static int32_t resolve_split(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ctx,
-                             int32_t split_tokens) {
-  if (split_tokens == 0) return pipelive_paged_attn_pick_split(kv, num_seqs, max_ctx);
-  if (split_tokens < 0 || split_tokens % 64 || split_tokens > max_split_tokens(kv)) return -1;
-  return split_tokens;
+static int32_t effective_max_ctx(const pipelive_kv_t *kv, int32_t table_stride, int32_t max_ctx) {
+  const int64_t table_cap = (int64_t)table_stride * kv->d.block_tokens;
+  if (max_ctx <= 0 || max_ctx > table_cap) return (int32_t)(table_cap > 0x7FFFFF00 ? 0x7FFFFF00 : table_cap);
+  return max_ctx;
 }
 
 size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
                                            int32_t max_ctx, int32_t split_tokens) {
   if (!kv || num_seqs <= 0 || max_ctx <= 0) return 256;
-  const int32_t st = resolve_split(kv, num_seqs, max_ctx, split_tokens);
-  if (st < 0) return 0;
-  const size_t splits = (size_t)((max_ctx + st - 1) / st);
-  const size_t rows = (size_t)num_seqs * kv->d.num_q_heads * splits;
-  return round_up(rows * kv->d.head_dim * 4, 256) + round_up(rows * 8, 256);
+  AttnShape sh;
+  if (!attn_shape(kv, num_seqs, max_ctx, split_tokens, &sh)) return 0;
+  const int G = kv->d.num_q_heads / kv->d.num_kv_heads;
+  return round_up((size_t)2 * sh.num_waves * attn_record_floats(G, kv->d.head_dim) * 4, 256);
 }
 
 int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
@@ -139,15 +152,14 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
                                    void *workspace, size_t workspace_bytes, void *stream) {
   if (!kv || !q || !out || !block_table || !ctx_lens) return PIPELIVE_E_INVAL;
   if (layer < 0 || layer >= kv->d.num_layers) return PIPELIVE_E_RANGE;
-  if (num_seqs < 0 || table_stride <= 0) return PIPELIVE_E_INVAL;
+  if (num_seqs < 0 || num_seqs > 65535 || table_stride <= 0) return PIPELIVE_E_INVAL;
   if (out_dtype != PIPELIVE_OUT_F32 && out_dtype != PIPELIVE_OUT_BF16) return PIPELIVE_E_INVAL;
-  if (!aligned(q, 16) || !aligned(out, 4)) return PIPELIVE_E_INVAL;
+  if (!aligned(q, 16) || !aligned(out, 16)) return PIPELIVE_E_INVAL;
   if (num_seqs == 0) return PIPELIVE_OK;
-  const int64_t table_cap = (int64_t)table_stride * kv->d.block_tokens;
-  if (max_ctx <= 0 || max_ctx > table_cap) max_ctx = (int32_t)(table_cap > 0x7FFFFFF0 ? 0x7FFFFFF0 : table_cap);
-  const int32_t st = resolve_split(kv, num_seqs, max_ctx, split_tokens);
-  if (st < 0) return PIPELIVE_E_INVAL;
-  const size_t need = pipelive_paged_attn_workspace_bytes(kv, num_seqs, max_ctx, st);
+  max_ctx = effective_max_ctx(kv, table_stride, max_ctx);
+  AttnShape sh;
+  if (!attn_shape(kv, num_seqs, max_ctx, split_tokens, &sh)) return PIPELIVE_E_INVAL;
+  const size_t need = pipelive_paged_attn_workspace_bytes(kv, num_seqs, max_ctx, split_tokens);
   if (!workspace || workspace_bytes < need || !aligned(workspace, 256)) return PIPELIVE_E_NOSPACE;
 
   AttnParams p;
@@ -166,14 +178,12 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
   p.G = p.Hq / p.Hkv;
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)kv->d.head_dim);
   p.scale_log2 = sc * 1.4426950408889634f;
-  p.split_tokens = st;
-  p.max_splits = (max_ctx + st - 1) / st;
-  const size_t rows = (size_t)num_seqs * p.Hq * p.max_splits;
-  p.ws_o = (float *)workspace;
-  p.ws_ml = (float *)((char *)workspace + round_up(rows * kv->d.head_dim * 4, 256));
+  p.num_waves = sh.num_waves;
+  p.tiles_per_wave = sh.tiles_per_wave;
+  p.ws = (float *)workspace;
   p.num_blocks = kv->d.num_blocks;
   p.status = &dev_state(kv)->status;
-  if (p.max_splits > 65535 || p.Hkv > 65535 || num_seqs > 65535) return PIPELIVE_E_INVAL;
+  if (p.Hq > 65535) return PIPELIVE_E_INVAL;
   HIP_TRY(launch_attn_decode(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));
   return PIPELIVE_OK;
 }

@@ -1,16 +1,27 @@
 // Paged-attention decode for gfx950 (CDNA4, wave64, MFMA).
 //
-// One workgroup of 4 waves per (split, KV head, sequence).  A wave walks its
-// share of the split in steps of 32 tokens.  Per step it fetches two 16-token
-// K tiles and the matching V^T tiles straight from HBM into the MFMA operand
-// registers (the in-block layout makes every load instruction cover whole
-// contiguous cache lines), computes S^T = K Q^T with v_mfma_f32_16x16x32_bf16
-// (rows = tokens, columns = the G query heads that share this KV head, padded
-// to 16), runs the online softmax on the accumulator layout, and accumulates
-// O^T += V^T P^T with P split into two bf16 terms so that no precision is
-// lost against fp32 weights.  The S^T accumulator layout (lane holds 4
-// consecutive tokens of one head) is exactly the B-operand layout of the PV
-// product, so scores never cross lanes except for the running max.
+// Work partition.  The unit of work is a *tile*: 32 consecutive tokens of one
+// (sequence, KV head).  All tiles of the batch, ordered by (sequence, KV head,
+// position), form one flat range that is cut into equal shares, one per wave,
+// so every wave streams the same number of KV bytes whatever the mix of
+// context lengths.  A share may cross (sequence, head) boundaries; a pair that
+// lies entirely inside one share is finished by that wave; a pair cut by a
+// share boundary leaves partial (m, l, O) records (at most two per wave) that
+// a small merge kernel combines in share order.  The partition and the merge
+// order are pure functions of the context lengths and of the share size, never
+// of addresses or of timing.
+//
+// Data path.  Per tile a wave fetches two 16-token K tiles and the matching
+// V^T tiles straight from HBM into MFMA operand registers (the in-block layout
+// makes every load instruction cover whole contiguous cache lines), double
+// buffered: the loads of tile i+1 are in flight while tile i is computed.
+// S^T = K Q^T uses v_mfma_f32_16x16x32_bf16 (rows = tokens, columns = the G
+// query heads sharing the KV head, padded to 16); the online softmax runs on
+// the accumulator layout; O^T += V^T P^T uses the same MFMA with P split into
+// two bf16 terms so nothing is lost against fp32 weights.  The S^T
+// accumulator layout (a lane holds 4 consecutive tokens of one head) is
+// exactly the B-operand layout of the PV product, so scores never cross lanes
+// except for the running max.
 //
 // Paper: Sec. 2 "LLM Inference" (decode re-reads the cached K/V: memory
 // bound), Sec. 5.1 (block addresses are resolved through the block table and
@@ -24,8 +35,9 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
-
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ uint64_t readlane64(uint64_t v, int lane) {
@@ -39,256 +51,476 @@ __device__ __forceinline__ uint32_t pack_hi16(float a, float b) {
   return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xFFFF0000u);
 }
 
-constexpr int kWaves = 4;
-constexpr int kMaxG = 16;
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float o) {
+  uint32_t u = __float_as_uint(o);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+constexpr int kTile = 32;      // tokens per tile
+constexpr int kSubTiles = 32;  // tiles whose block addresses are resolved at once
+
+__device__ __forceinline__ int tiles_of(int n, int max_ctx) {
+  if (n > max_ctx) n = max_ctx;
+  return n <= 0 ? 0 : (n + kTile - 1) / kTile;
+}
+
+// KV blocks are reached through 64-bit addresses read from the block list; the
+// explicit global address space keeps the loads global_load (not flat_load).
+typedef const u32x4 __attribute__((address_space(1))) *global_u4;
+typedef const u32x2 __attribute__((address_space(1))) *global_u2;
+
+template <int D>
+struct KRegs {
+  u32x4 k[2][D / 32];
+  int nvalid[2];
+};
+template <int D>
+struct VRegs {
+  u32x2 v[D / 16][2];
+};
+
+// Issue the K loads of one tile.  a0/a1 are the (wave-uniform) block addresses
+// of its two 16-token halves (both always valid memory: a half without tokens
+// re-reads the first half's block and is masked), nv0/nv1 the number of valid
+// tokens in each half.
+template <int D, int BS>
+__device__ __forceinline__ void load_k(KRegs<D> &t, uint64_t a0, uint64_t a1, int nv0, int nv1, int g,
+                                       int r, int qg) {
+  constexpr int NC = D / 32;
+  constexpr int KHEAD = BS * D * 2;
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    const uint64_t addr = T ? a1 : a0;
+    const int nv = T ? nv1 : nv0;
+    t.nvalid[T] = nv > 0 ? nv : 0;
+    const int toff = (BS == 32) ? 16 * T : 0;
+    const uint64_t kb = addr + (uint64_t)g * KHEAD + (uint32_t)((qg * BS + toff + r) * 16);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) t.k[T][c] = *(global_u4)(kb + (uint32_t)(4 * c * BS * 16));
+  }
+}
 
 template <int D, int BS>
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnParams p) {
-  constexpr int NC = D / 32;  // QK^T: 32 head-dim elements per MFMA
-  constexpr int ND = D / 16;  // PV: 16 output dims per MFMA
-  constexpr int KHEAD = BS * D * 2;  // bytes of one head's K (or V) in a block
-
-  const int sp = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
-  int n = p.ctx[s];
-  if (n > p.max_ctx) n = p.max_ctx;
-  const int ST = p.split_tokens;
-  const int c0 = sp * ST;
-  if (c0 >= n) return;
-  const int c1 = min(n, c0 + ST);
-  const int nsplit = (n + ST - 1) / ST;
-
-  const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform
-  const int r = lane & 15, qg = lane >> 4;
-  const int G = p.G;
-
-  // resolve this split's blocks: one block per lane (ST <= 64 * BS)
-  const int nblk = (c1 - c0 + BS - 1) / BS;
-  uint64_t my_addr = 0;
-  if (lane < nblk) {
-    int id = p.table[(int64_t)s * p.table_stride + c0 / BS + lane];
-    if ((uint32_t)id < (uint64_t)p.num_blocks) {
-      my_addr = p.block_list[id] + p.layer_off;
-    } else {
-      atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
-    }
+__device__ __forceinline__ void load_v(VRegs<D> &t, uint64_t a0, uint64_t a1, int g, int Hkv, int r,
+                                       int qg) {
+  constexpr int ND = D / 16;
+  constexpr int KHEAD = BS * D * 2;
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    const uint64_t addr = T ? a1 : a0;
+    const int toff = (BS == 32) ? 16 * T : 0;
+    const uint64_t vb = addr + (uint64_t)(Hkv + g) * KHEAD + (uint32_t)((r * BS + toff + 4 * qg) * 2);
+#pragma unroll
+    for (int c = 0; c < ND; ++c) t.v[c][T] = *(global_u2)(vb + (uint32_t)(16 * c * BS * 2));
   }
+}
 
-  // Q^T operand: lane (head = r, k-group qg) holds q[head][32c + 8qg .. +7]
-  bf16x8 qreg[NC];
-  {
-    const uint16_t *qp = p.q + ((int64_t)s * p.Hq + (int64_t)g * G + r) * D + 8 * qg;
+// S^T = K Q^T, online softmax update; returns the P^T operand as two bf16 terms.
+template <int D>
+__device__ __forceinline__ void qk_softmax(const KRegs<D> &t, const bf16x8 (&qreg)[D / 32],
+                                           f32x4 (&acc)[D / 16], float &m, float &l, float scale_log2,
+                                           int qg, u32x4 &ph, u32x4 &pl) {
+  constexpr int NC = D / 32, ND = D / 16;
+  f32x4 sc[2];
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (r < G) v = *(const uint4 *)(qp + 32 * c);
-      qreg[c] = as_bf16x8(v);
-    }
+  for (int T = 0; T < 2; ++T) {
+    sc[T] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+      sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[T][c]), qreg[c], sc[T], 0, 0, 0);
   }
+  // scale; mask by predicate, never by arithmetic: unused slots may hold NaN
+  float x[8];
+  float mloc = -INFINITY;
+#pragma unroll
+  for (int T = 0; T < 2; ++T)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = (4 * qg + i) < t.nvalid[T];
+      const float v = ok ? sc[T][i] * scale_log2 : -INFINITY;
+      x[4 * T + i] = v;
+      mloc = fmaxf(mloc, v);
+    }
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
+  mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
+  const float m_new = fmaxf(m, mloc);  // finite: the tile holds at least one valid token
+  const float alpha = fast_exp2(m - m_new);
+  float pv[8], psum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    pv[i] = fast_exp2(x[i] - m_new);
+    psum += pv[i];
+  }
+  l = l * alpha + psum;
+  m = m_new;
+  if (__any(alpha != 1.0f)) {
+#pragma unroll
+    for (int c = 0; c < ND; ++c) acc[c] *= alpha;
+  }
+  // P^T operand: slots 0..3 = half 0 tokens 4qg+i, slots 4..7 = half 1; two bf16 terms
+  float lo[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) lo[i] = pv[i] - __uint_as_float(__float_as_uint(pv[i]) & 0xFFFF0000u);
+  ph = (u32x4){pack_hi16(pv[0], pv[1]), pack_hi16(pv[2], pv[3]), pack_hi16(pv[4], pv[5]),
+               pack_hi16(pv[6], pv[7])};
+  pl = (u32x4){pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
+               pack_hi16(lo[6], lo[7])};
+}
 
-  f32x4 acc[ND];
+// O^T += V^T P^T.  nv0/nv1: valid tokens of the two halves (as recorded by load_k).
+template <int D>
+__device__ __forceinline__ void pv_accumulate(VRegs<D> &t, int nv0, int nv1, u32x4 ph, u32x4 pl,
+                                              f32x4 (&acc)[D / 16], int qg) {
+  constexpr int ND = D / 16;
+  // V of masked tokens must be zero (0 * NaN is NaN): partial halves only
 #pragma unroll
-  for (int c = 0; c < ND; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m = -INFINITY, l = 0.f;
-
-  const int nsteps = (c1 - c0 + 31) / 32;
-  for (int st = w; st < nsteps; st += kWaves) {
-    const int t0 = c0 + 32 * st;
-    uint4 kreg[2][NC];
-    uint2 vreg[ND][2];
-    int nvalid[2];
-#pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      const int tile_start = t0 + 16 * T;
-      nvalid[T] = c1 - tile_start;  // > 0: tile holds valid tokens
-      const int bidx = (BS == 16) ? (2 * st + T) : st;
-      const uint64_t addr = readlane64(my_addr, bidx);
-      const bool on = nvalid[T] > 0 && addr != 0;
-      if (!on) nvalid[T] = 0;
-      const int toff = (BS == 32) ? 16 * T : 0;
-      const char *kb = (const char *)addr + (int64_t)g * KHEAD;
-      const char *vb = (const char *)addr + (int64_t)p.Hkv * KHEAD + (int64_t)g * KHEAD;
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        kreg[T][c] = make_uint4(0, 0, 0, 0);
-        if (on) kreg[T][c] = *(const uint4 *)(kb + (((4 * c + qg) * BS + toff + r) * 16));
-      }
+  for (int T = 0; T < 2; ++T) {
+    const int nv = T ? nv1 : nv0;
+    if (nv < 16) {
+      const int keep = min(max(nv - 4 * qg, 0), 4);
+      const uint64_t mask = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
 #pragma unroll
       for (int c = 0; c < ND; ++c) {
-        vreg[c][T] = make_uint2(0, 0);
-        if (on) vreg[c][T] = *(const uint2 *)(vb + (((16 * c + r) * BS + toff + 4 * qg) * 2));
+        t.v[c][T].x &= (uint32_t)mask;
+        t.v[c][T].y &= (uint32_t)(mask >> 32);
       }
     }
+  }
+#pragma unroll
+  for (int c = 0; c < ND; ++c) {
+    const bf16x8 va = as_bf16x8((u32x4){t.v[c][0].x, t.v[c][0].y, t.v[c][1].x, t.v[c][1].y});
+    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(ph), acc[c], 0, 0, 0);
+    acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(pl), acc[c], 0, 0, 0);
+  }
+}
 
-    if (nvalid[0] <= 0 && nvalid[1] <= 0) continue;  // only after a bad block id
+// ---- the partition of the flat tile range [0, total) into per-wave shares.
+// Fixed mode (tiles_per_wave > 0): wave w owns [w*Q, (w+1)*Q).
+// Balanced mode: total = nw*Qf + rem; the first `rem` waves own Qf+1 tiles, the
+// others Qf, so no wave carries more than one tile above the mean.
+__device__ __forceinline__ int64_t share_start(const AttnParams &p, int64_t total, int64_t w) {
+  if (p.tiles_per_wave > 0) return w * p.tiles_per_wave;
+  const int64_t qf = total / p.num_waves, rem = total % p.num_waves;
+  return w * qf + (w < rem ? w : rem);
+}
+__device__ __forceinline__ int64_t share_wave(const AttnParams &p, int64_t total, int64_t t) {
+  if (p.tiles_per_wave > 0) return t / p.tiles_per_wave;
+  const int64_t qf = total / p.num_waves, rem = total % p.num_waves;
+  const int64_t big = rem * (qf + 1);
+  if (t < big) return t / (qf + 1);
+  return rem + (t - big) / qf;  // qf > 0 here because t < total
+}
 
-    // S^T tiles: rows = tokens, columns = heads
-    f32x4 sc[2];
-#pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      sc[T] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < NC; ++c)
-        sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[T][c]), qreg[c], sc[T], 0, 0, 0);
-    }
+template <int D, int BS>
+__global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
+  constexpr int NC = D / 32, ND = D / 16;
+  const int lane = threadIdx.x & 63;
+  const int gw = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int r = lane & 15, qg = lane >> 4;
+  const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
+  if (gw >= p.num_waves) return;
 
-    // scale, mask by predicate (never by arithmetic: unused slots may hold NaN)
-    float x[8];
-    float mloc = -INFINITY;
-#pragma unroll
-    for (int T = 0; T < 2; ++T)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool ok = (4 * qg + i) < nvalid[T];
-        float v = ok ? sc[T][i] * p.scale_log2 : -INFINITY;
-        x[4 * T + i] = v;
-        mloc = fmaxf(mloc, v);
+  // ---- total number of tiles; rows of sequences without tokens are zeroed here
+  int64_t carry = 0;
+  for (int base = 0; base < S; base += 64) {
+    const int n_raw = (base + lane < S) ? p.ctx[base + lane] : 0;
+    if (gw == 0 && n_raw > p.max_ctx) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
+    const int ti = tiles_of(n_raw, p.max_ctx);
+    const int inc = wave_inclusive_scan(ti, lane);
+    carry += __builtin_amdgcn_readlane(inc, 63);
+  }
+  const int64_t total = carry * Hkv;
+  for (int s0 = gw; s0 < S; s0 += p.num_waves) {
+    if (tiles_of(p.ctx[s0], p.max_ctx) == 0) {
+      for (int e = lane; e < p.Hq * D; e += 64) {
+        if (p.out_dtype == PIPELIVE_OUT_F32) ((float *)p.out)[(int64_t)s0 * p.Hq * D + e] = 0.f;
+        else ((uint16_t *)p.out)[(int64_t)s0 * p.Hq * D + e] = 0;
       }
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-    mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-    const float m_new = fmaxf(m, mloc);  // finite: the step holds at least one valid token
-    const float alpha = fast_exp2(m - m_new);
-    float pv[8], psum = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      pv[i] = fast_exp2(x[i] - m_new);
-      psum += pv[i];
     }
-    l = l * alpha + psum;
-    m = m_new;
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-      for (int c = 0; c < ND; ++c) acc[c] *= alpha;
-    }
+  }
+  const int64_t a = share_start(p, total, gw);
+  const int64_t b0 = share_start(p, total, (int64_t)gw + 1);
+  const int64_t b = b0 < total ? b0 : total;
+  if (a >= b) return;
 
-    // P^T operand: slots 0..3 = tile 0 tokens 4qg+i, slots 4..7 = tile 1; two bf16 terms
-    uint4 ph, pl;
+  // first sequence whose flat start is <= a (sequences without tokens never match last)
+  int s = 0;
+  int64_t P_s = 0;  // tiles of all sequences before s
+  carry = 0;
+  for (int base = 0; base < S; base += 64) {
+    const bool in = base + lane < S;
+    const int ti = in ? tiles_of(p.ctx[base + lane], p.max_ctx) : 0;
+    const int inc = wave_inclusive_scan(ti, lane);
+    const int64_t excl = carry + inc - ti;
+    const uint64_t bal = __ballot(in && excl * Hkv <= a);
+    const int cnt = __popcll(bal);
+    if (cnt > 0) {
+      s = base + cnt - 1;
+      P_s = carry + (__builtin_amdgcn_readlane(inc, cnt - 1) - __builtin_amdgcn_readlane(ti, cnt - 1));
+    }
+    carry += __builtin_amdgcn_readlane(inc, 63);
+  }
+
+  const int64_t rec_sz = attn_record_floats(G, D);
+
+  int64_t t = a;
+  while (t < b) {
+    // (s, g, j): sequence, KV head, tile inside the sequence of flat position t
+    int n = p.ctx[s];
+    if (n > p.max_ctx) n = p.max_ctx;
+    const int ts = tiles_of(n, p.max_ctx);
+    const int64_t rem = t - P_s * Hkv;
+    if (ts == 0 || rem >= (int64_t)ts * Hkv) {  // step to the next sequence
+      P_s += ts;
+      ++s;
+      continue;
+    }
+    const int g = (int)(rem / ts);
+    const int j0 = (int)(rem % ts);
+    const int cnt = (int)min((int64_t)(ts - j0), b - t);  // tiles of this pair inside the share
+    const int64_t T0 = t - j0;                            // flat start of the pair
+
+    // Q^T operand: lane (head = r, k-group qg) holds q[head][32c + 8qg .. +7]
+    bf16x8 qreg[NC];
     {
-      float lo[8];
+      const uint16_t *qp = p.q + ((int64_t)s * p.Hq + (int64_t)g * G + r) * D + 8 * qg;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) lo[i] = pv[i] - __uint_as_float(__float_as_uint(pv[i]) & 0xFFFF0000u);
-      ph = make_uint4(pack_hi16(pv[0], pv[1]), pack_hi16(pv[2], pv[3]), pack_hi16(pv[4], pv[5]),
-                      pack_hi16(pv[6], pv[7]));
-      pl = make_uint4(pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
-                      pack_hi16(lo[6], lo[7]));
+      for (int c = 0; c < NC; ++c) {
+        u32x4 v = {0, 0, 0, 0};
+        if (r < G) v = *(const u32x4 *)(qp + 32 * c);
+        qreg[c] = as_bf16x8(v);
+      }
+    }
+    f32x4 acc[ND];
+#pragma unroll
+    for (int c = 0; c < ND; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    for (int sub = 0; sub < cnt; sub += kSubTiles) {
+      const int jb = j0 + sub;                        // first tile of this batch
+      const int nt = min(cnt - sub, kSubTiles);       // tiles in this batch
+      // resolve the batch's blocks: one block per lane
+      constexpr int BPT = kTile / BS;                 // blocks per tile: 2 or 1
+      const int first_blk = jb * BPT;
+      const int nblk = min(nt * BPT, (n + BS - 1) / BS - first_blk);
+      uint64_t my_addr = 0;
+      bool bad = false;
+      if (lane < nblk) {
+        const int id = p.table[(int64_t)s * p.table_stride + first_blk + lane];
+        if ((uint32_t)id < (uint64_t)p.num_blocks) my_addr = p.block_list[id] + p.layer_off;
+        else bad = true;
+      }
+      if (__any(bad)) {  // never dereference a bad id: flag it and leave these tokens out
+        if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
+        continue;
+      }
+      // tile i of the batch: block addresses and valid-token counts of its halves
+      auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
+        const int tok0 = (jb + i) * kTile;
+        if (BS == 16) {
+          a0 = readlane64(my_addr, 2 * i);
+          a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
+        } else {
+          a0 = a1 = readlane64(my_addr, i);
+        }
+        nv0 = min(n - tok0, 16);
+        nv1 = min(n - tok0 - 16, 16);
+      };
+      // Software pipeline: K of tile i+1 is requested before the QK^T of tile i,
+      // V of tile i+1 before the PV of tile i.
+      KRegs<D> kc, kn;
+      VRegs<D> vc, vn;
+      uint64_t a0, a1;
+      int nv0, nv1;
+      addr_of(0, a0, a1, nv0, nv1);
+      load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
+      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
+#pragma unroll 1
+      for (int i = 0; i + 1 < nt; ++i) {
+        addr_of(i + 1, a0, a1, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
+        u32x4 ph, pl;
+        qk_softmax<D>(kc, qreg, acc, m, l, p.scale_log2, qg, ph, pl);
+        load_v<D, BS>(vn, a0, a1, g, Hkv, r, qg);
+        pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
+        kc = kn;
+        vc = vn;
+      }
+      {  // last tile of the batch: nothing left to prefetch
+        u32x4 ph, pl;
+        qk_softmax<D>(kc, qreg, acc, m, l, p.scale_log2, qg, ph, pl);
+        pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
+      }
     }
 
-    // V of masked tokens must be zero (0 * NaN is NaN): partial tiles only
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int64_t row = (int64_t)s * p.Hq + (int64_t)g * G + r;
+    // lane (qg, r) holds O[head r][16c + 4qg + i]
+    auto store_out = [&](const f32x4 (&o)[ND], float inv) {
+      if (r >= G) return;
+      if (p.out_dtype == PIPELIVE_OUT_F32) {
+        float *dst = (float *)p.out + row * D + 4 * qg;
 #pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      if (nvalid[T] > 0 && nvalid[T] < 16) {
-        const int keep = min(max(nvalid[T] - 4 * qg, 0), 4);
-        const uint64_t mask = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
+        for (int c = 0; c < ND; ++c)
+          *(float4 *)(dst + 16 * c) = make_float4(o[c][0] * inv, o[c][1] * inv, o[c][2] * inv, o[c][3] * inv);
+      } else {
+        uint16_t *dst = (uint16_t *)p.out + row * D + 4 * qg;
 #pragma unroll
         for (int c = 0; c < ND; ++c) {
-          vreg[c][T].x &= (uint32_t)mask;
-          vreg[c][T].y &= (uint32_t)(mask >> 32);
+          const uint32_t w0 = f32_to_bf16_rne(o[c][0] * inv) | ((uint32_t)f32_to_bf16_rne(o[c][1] * inv) << 16);
+          const uint32_t w1 = f32_to_bf16_rne(o[c][2] * inv) | ((uint32_t)f32_to_bf16_rne(o[c][3] * inv) << 16);
+          *(uint2 *)(dst + 16 * c) = make_uint2(w0, w1);
+        }
+      }
+    };
+    const bool complete = (j0 == 0) && (j0 + cnt == ts);
+    if (complete) {
+      store_out(acc, l > 0.f ? 1.0f / l : 0.f);  // l == 0 only after a bad block id
+    } else {
+      // The pair is cut by a share boundary.  Leave a partial record O[G][D], m[G],
+      // l[G] for the merge kernel: the pair that began before this share uses slot
+      // 2*gw, a pair that runs past its end uses slot 2*gw+1.
+      const int64_t slot = 2 * (int64_t)gw + (T0 <= a ? 0 : 1);
+      float *rec = p.ws + slot * rec_sz;
+      if (r < G) {
+        float *o = rec + (int64_t)r * D + 4 * qg;
+#pragma unroll
+        for (int c = 0; c < ND; ++c)
+          *(float4 *)(o + 16 * c) = make_float4(acc[c][0], acc[c][1], acc[c][2], acc[c][3]);
+        if (qg == 0) {
+          rec[(int64_t)G * D + r] = m;
+          rec[(int64_t)G * D + G + r] = l;
         }
       }
     }
-
-#pragma unroll
-    for (int c = 0; c < ND; ++c) {
-      const bf16x8 va = as_bf16x8(make_uint4(vreg[c][0].x, vreg[c][0].y, vreg[c][1].x, vreg[c][1].y));
-      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(ph), acc[c], 0, 0, 0);
-      acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(pl), acc[c], 0, 0, 0);
-    }
+    t += cnt;
   }
+}
 
-  l += __shfl_xor(l, 16);
-  l += __shfl_xor(l, 32);
-
-  // merge the 4 waves through LDS
-  __shared__ float sh_o[kWaves][kMaxG][D];
-  __shared__ float sh_m[kWaves][kMaxG];
-  __shared__ float sh_l[kWaves][kMaxG];
-  if (r < G) {
-#pragma unroll
-    for (int c = 0; c < ND; ++c)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) sh_o[w][r][16 * c + 4 * qg + i] = acc[c][i];
-    if (qg == 0) {
-      sh_m[w][r] = m;
-      sh_l[w][r] = l;
+// Merge kernel: one wave per (sequence, KV head) pair that was cut by share
+// boundaries.  Records are merged in share order, so the result does not depend
+// on which wave finished first.  Lane e handles the float4 at element
+// 4*lane + 256*j of the pair's [G][D] output.
+template <int D, int NJ>
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
+  const int lane = threadIdx.x & 63;
+  const int pair = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
+  if (pair >= S * Hkv) return;
+  const int s = pair / Hkv, g = pair % Hkv;
+  // tiles before sequence s and in total
+  int64_t carry = 0, before = 0;
+  for (int base = 0; base < S; base += 64) {
+    const int ti = (base + lane < S) ? tiles_of(p.ctx[base + lane], p.max_ctx) : 0;
+    const int inc = wave_inclusive_scan(ti, lane);
+    if (s >= base && s < base + 64) {
+      const int k = s - base;
+      before = carry + (__builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(ti, k));
     }
+    carry += __builtin_amdgcn_readlane(inc, 63);
   }
-  __syncthreads();
-  for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-    const int hh = idx / D, d = idx % D;
-    float M = sh_m[0][hh];
+  const int64_t total = carry * Hkv;
+  const int ts = tiles_of(p.ctx[s], p.max_ctx);
+  if (ts == 0) return;  // zero row, written by the main kernel
+  const int64_t T0 = before * Hkv + (int64_t)g * ts;
+  const int64_t w_first = share_wave(p, total, T0), w_last = share_wave(p, total, T0 + ts - 1);
+  if (w_first == w_last) return;  // finished by the wave that owns it
+  const int64_t rec_sz = attn_record_floats(G, D);
+  const int GD = G * D;
+  float M[NJ], L[NJ];
+  float4 O[NJ];
 #pragma unroll
-    for (int k = 1; k < kWaves; ++k) M = fmaxf(M, sh_m[k][hh]);
-    float L = 0.f, O = 0.f;
+  for (int j = 0; j < NJ; ++j) {
+    M[j] = -INFINITY;
+    L[j] = 0.f;
+    O[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  constexpr int kChunk = 4;  // records fetched together, merged in order
+  for (int64_t w0 = w_first; w0 <= w_last; w0 += kChunk) {
+    float mw[kChunk][NJ], lw[kChunk][NJ];
+    float4 ow[kChunk][NJ];
 #pragma unroll
-    for (int k = 0; k < kWaves; ++k) {
-      const float wk = fast_exp2(sh_m[k][hh] - M);  // -inf (idle wave) -> 0
-      L += wk * sh_l[k][hh];
-      O += wk * sh_o[k][hh][d];
-    }
-    const int64_t row = (int64_t)s * p.Hq + (int64_t)g * G + hh;
-    if (nsplit == 1) {
-      const float o = O / L;
-      if (p.out_dtype == PIPELIVE_OUT_F32) {
-        ((float *)p.out)[row * D + d] = o;
-      } else {
-        uint32_t u = __float_as_uint(o);
-        u += 0x7FFFu + ((u >> 16) & 1u);
-        ((uint16_t *)p.out)[row * D + d] = (uint16_t)(u >> 16);
+    for (int u = 0; u < kChunk; ++u) {
+      const int64_t w = w0 + u < w_last ? w0 + u : w_last;  // clamp: re-reads the last record, unused
+      const float *rw = p.ws + (2 * w + (T0 <= share_start(p, total, w) ? 0 : 1)) * rec_sz;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const int e = 4 * lane + 256 * j;
+        const int ec = e < GD ? e : 0;
+        mw[u][j] = rw[GD + ec / D];
+        lw[u][j] = rw[GD + G + ec / D];
+        ow[u][j] = *(const float4 *)(rw + ec);
       }
-    } else {
-      p.ws_o[(row * p.max_splits + sp) * D + d] = O;
-      if (d == 0) {
-        p.ws_ml[(row * p.max_splits + sp) * 2 + 0] = M;
-        p.ws_ml[(row * p.max_splits + sp) * 2 + 1] = L;
+    }
+#pragma unroll
+    for (int u = 0; u < kChunk; ++u) {
+      if (w0 + u > w_last) break;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const float Mn = fmaxf(M[j], mw[u][j]);
+        const float fa = (M[j] == -INFINITY) ? 0.f : fast_exp2(M[j] - Mn);
+        const float fb = (mw[u][j] == -INFINITY) ? 0.f : fast_exp2(mw[u][j] - Mn);
+        L[j] = L[j] * fa + lw[u][j] * fb;
+        O[j] = make_float4(O[j].x * fa + ow[u][j].x * fb, O[j].y * fa + ow[u][j].y * fb,
+                           O[j].z * fa + ow[u][j].z * fb, O[j].w * fa + ow[u][j].w * fb);
+        M[j] = Mn;
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int e = 4 * lane + 256 * j;
+    if (e < GD) {
+      const float inv = L[j] > 0.f ? 1.0f / L[j] : 0.f;
+      const int64_t idx = ((int64_t)s * p.Hq + (int64_t)g * G) * D + e;
+      if (p.out_dtype == PIPELIVE_OUT_F32) {
+        *(float4 *)((float *)p.out + idx) = make_float4(O[j].x * inv, O[j].y * inv, O[j].z * inv, O[j].w * inv);
+      } else {
+        const uint32_t w0 = f32_to_bf16_rne(O[j].x * inv) | ((uint32_t)f32_to_bf16_rne(O[j].y * inv) << 16);
+        const uint32_t w1 = f32_to_bf16_rne(O[j].z * inv) | ((uint32_t)f32_to_bf16_rne(O[j].w * inv) << 16);
+        *(uint2 *)((uint16_t *)p.out + idx) = make_uint2(w0, w1);
       }
     }
   }
 }
 
-// Merge the per-split partial results of one (sequence, head): fixed order, so
-// the result does not depend on which workgroup finished first.
 template <int D>
-__global__ __launch_bounds__(D) void attn_combine_kernel(AttnParams p) {
-  const int h = blockIdx.x, s = blockIdx.y, d = threadIdx.x;
-  int n = p.ctx[s];
-  if (n > p.max_ctx) {
-    n = p.max_ctx;
-    if (d == 0 && h == 0) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
-  }
-  const int nsplit = (n + p.split_tokens - 1) / p.split_tokens;
-  if (nsplit == 1) return;  // written by the main kernel
-  const int64_t row = (int64_t)s * p.Hq + h;
-  float o = 0.f;
-  if (nsplit > 1) {
-    const float *ml = p.ws_ml + row * p.max_splits * 2;
-    const float *wo = p.ws_o + row * p.max_splits * D;
-    float M = -INFINITY;
-    for (int k = 0; k < nsplit; ++k) M = fmaxf(M, ml[2 * k]);
-    float L = 0.f, O = 0.f;
-    for (int k = 0; k < nsplit; ++k) {
-      const float wk = fast_exp2(ml[2 * k] - M);
-      L += wk * ml[2 * k + 1];
-      O += wk * wo[(int64_t)k * D + d];
-    }
-    o = O / L;
-  }
-  if (p.out_dtype == PIPELIVE_OUT_F32) {
-    ((float *)p.out)[row * D + d] = o;
-  } else {
-    uint32_t u = __float_as_uint(o);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    ((uint16_t *)p.out)[row * D + d] = (uint16_t)(u >> 16);
-  }
+hipError_t launch_merge(const AttnParams &p, hipStream_t st) {
+  const unsigned mgrid = (unsigned)(((int64_t)p.num_seqs * p.Hkv + 3) / 4);
+  const int nj = (p.G * D + 255) / 256;
+  if (nj <= 1) hipLaunchKernelGGL((attn_merge_kernel<D, 1>), dim3(mgrid), dim3(256), 0, st, p);
+  else if (nj <= 2) hipLaunchKernelGGL((attn_merge_kernel<D, 2>), dim3(mgrid), dim3(256), 0, st, p);
+  else if (nj <= 4) hipLaunchKernelGGL((attn_merge_kernel<D, 4>), dim3(mgrid), dim3(256), 0, st, p);
+  else hipLaunchKernelGGL((attn_merge_kernel<D, 8>), dim3(mgrid), dim3(256), 0, st, p);
+  return hipGetLastError();
 }
 
 template <int D, int BS>
 hipError_t launch_t(const AttnParams &p, hipStream_t st) {
-  dim3 grid(p.max_splits, p.Hkv, p.num_seqs);
-  hipLaunchKernelGGL((attn_decode_kernel<D, BS>), grid, dim3(256), 0, st, p);
+  const unsigned grid = (unsigned)((p.num_waves + 3) / 4);
+  hipLaunchKernelGGL((attn_decode_kernel<D, BS>), dim3(grid), dim3(256), 0, st, p);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((attn_combine_kernel<D>), dim3(p.Hq, p.num_seqs), dim3(D), 0, st, p);
-  return hipGetLastError();
+  return launch_merge<D>(p, st);
+}
+
+template <int D, int BS>
+int occupancy_t() {
+  int nb = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, attn_decode_kernel<D, BS>, 256, 0) != hipSuccess || nb < 1)
+    nb = 2;
+  return nb * 4;  // waves per CU
 }
 
 }  // namespace
@@ -299,6 +531,18 @@ hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st
   if (D == 64 && BS == 16) return launch_t<64, 16>(p, st);
   if (D == 64 && BS == 32) return launch_t<64, 32>(p, st);
   return hipErrorInvalidValue;
+}
+
+int attn_waves_per_cu(int D, int BS) {
+  static int cache[4] = {0, 0, 0, 0};
+  const int idx = (D == 128 ? 0 : 2) + (BS == 16 ? 0 : 1);
+  if (cache[idx] == 0) {
+    if (D == 128 && BS == 16) cache[idx] = occupancy_t<128, 16>();
+    else if (D == 128 && BS == 32) cache[idx] = occupancy_t<128, 32>();
+    else if (D == 64 && BS == 16) cache[idx] = occupancy_t<64, 16>();
+    else cache[idx] = occupancy_t<64, 32>();
+  }
+  return cache[idx];
 }
 
 }  // namespace pipelive

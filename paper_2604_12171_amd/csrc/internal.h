@@ -53,13 +53,18 @@ struct AttnParams {
   int32_t num_seqs, max_ctx;
   int32_t Hq, Hkv, G;
   float scale_log2;  // scale * log2(e)
-  int32_t split_tokens, max_splits;
-  float *ws_o;   // [S][Hq][max_splits][D]
-  float *ws_ml;  // [S][Hq][max_splits][2]
+  int32_t num_waves;       // waves launched
+  int32_t tiles_per_wave;  // share size in 32-token tiles; 0 = total / num_waves
+  float *ws;               // partial records: [2 * num_waves][attn_record_floats(G, D)]
   int64_t num_blocks;
   int32_t *status;
 };
+// floats of one partial record: O[G][D], m[G], l[G], padded to 16 bytes
+__host__ __device__ inline int64_t attn_record_floats(int G, int D) {
+  return (int64_t)G * D + ((2 * G + 3) & ~3);
+}
 hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st);
+int attn_waves_per_cu(int D, int BS);
 
 // ---- resize
 struct TableRef {
