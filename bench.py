@@ -52,6 +52,7 @@ def parse_args():
     ap.add_argument("--mig-layers", type=int, default=4, help="layers carried by each patch")
     ap.add_argument("--pool-blocks", type=int, default=0, help="override the pool size (blocks per layer)")
     ap.add_argument("--shrink", type=float, default=0.20)
+    ap.add_argument("--bulk-fraction", type=float, default=0.20, help="dirty fraction of the bulk patch round")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers in the CPU oracle sample")
     ap.add_argument("--decode-only", action="store_true", help="profiling aid: steps run phase 1 only")
@@ -144,7 +145,7 @@ def main():
     # migration target: a compact region reached through a block map
     Lm = min(args.mig_layers, L)
     mig_layers = list(range(L - Lm, L))
-    target = P.KVRegion(Lm, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
+    target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
                         n_live, arenas=2)
     dst_map = torch.full((B,), -1, dtype=torch.int32)
     dst_map[torch.from_numpy(batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
@@ -186,7 +187,7 @@ def main():
         P.pipelive_kv_patch_collect(region, mig_layers, patch)
         if events:
             events[2].record()
-        P.pipelive_kv_patch_apply(target, list(range(Lm)), patch, dst_block_map=dst_map)
+        P.pipelive_kv_patch_apply(target, mig_layers, patch, dst_block_map=dst_map)
         if events:
             events[3].record()
         rc, res = P.pipelive_kv_resize(region, B_new, [table_d], [used_d], workspace=rws)
@@ -259,6 +260,40 @@ def main():
             "us": round(rsz_avg * 1e3, 1), "GBps": round(resize_bytes / (rsz_avg * 1e-3) / 1e9, 1),
             "frac_of_peak": round(resize_bytes / (rsz_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         result["switch_us"] = round((col_avg + app_avg + rsz_avg) * 1e3, 1)
+
+    # ---------------- bulk patch round (the patch GB/s figure): 20 % of the live blocks, all layers
+    if not args.decode_only:
+        bulk_ids_np = pin.draw_dirty_ids(batch, seed, 1, args.bulk_fraction)
+        bulk_ids = torch.from_numpy(bulk_ids_np.astype(np.int32)).cuda()
+        nb = int(bulk_ids.numel())
+        all_layers = list(range(L))
+        bulk_cap = 64 + 256 + nb * (4 + L * cfg.blk_bytes) + 4096
+        bulk_patch = torch.empty(bulk_cap, dtype=torch.uint8, device="cuda")
+        bulk_payload = nb * L * cfg.blk_bytes
+        tc, ta = [], []
+        for it in range(6):
+            e0, e1, e2 = ev(), ev(), ev()
+            P.pipelive_kv_mark_dirty(region, bulk_ids, 0)
+            e0.record()
+            P.pipelive_kv_patch_collect(region, all_layers, bulk_patch)
+            e1.record()
+            P.pipelive_kv_patch_apply(target, all_layers, bulk_patch, dst_block_map=dst_map)
+            e2.record()
+            torch.cuda.synchronize()
+            if it:
+                tc.append(e0.elapsed_time(e1))
+                ta.append(e1.elapsed_time(e2))
+        tcm, tam = sum(tc) / len(tc), sum(ta) / len(ta)
+        result["patch_bulk"] = {
+            "dirty_blocks": nb, "layers": L, "payload_bytes": int(bulk_payload),
+            "collect_us": round(tcm * 1e3, 1), "collect_GBps": round(2 * bulk_payload / (tcm * 1e-3) / 1e9, 1),
+            "collect_frac_of_peak": round(2 * bulk_payload / (tcm * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "apply_us": round(tam * 1e3, 1), "apply_GBps": round(2 * bulk_payload / (tam * 1e-3) / 1e9, 1),
+            "apply_frac_of_peak": round(2 * bulk_payload / (tam * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        st = P.pipelive_kv_read_state(target)
+        if st.status != 0 or P.pipelive_kv_read_state(region).status != 0:
+            raise RuntimeError("device status word set during the bench")
+        del bulk_patch
 
     # ---------------- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
