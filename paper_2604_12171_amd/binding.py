@@ -296,7 +296,7 @@ class KVRegion:
 
     def write_blocks(self, layer: int, block_ids, data: torch.Tensor) -> None:
         """data: int16 [n][blk_elems] on the device -> blocks ``block_ids`` of ``layer``."""
-        ids = torch.as_tensor(block_ids, dtype=torch.int64)
+        ids = torch.tensor([int(b) for b in block_ids], dtype=torch.int64)
         o = (layer % self.stack_k) * self.blk_elems
         for a in range(self._n_ar):
             sel = (ids % self._n_ar) == a
@@ -306,7 +306,7 @@ class KVRegion:
                 t[rows, o:o + self.blk_elems] = data[sel.to(data.device)]
 
     def read_blocks(self, layer: int, block_ids) -> torch.Tensor:
-        ids = torch.as_tensor(block_ids, dtype=torch.int64)
+        ids = torch.tensor([int(b) for b in block_ids], dtype=torch.int64)
         out = torch.empty((len(ids), self.blk_elems), dtype=torch.int16, device=self.device)
         o = (layer % self.stack_k) * self.blk_elems
         for a in range(self._n_ar):
