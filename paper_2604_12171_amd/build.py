@@ -34,11 +34,12 @@ def stale() -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build_lib(force: bool = False, verbose: bool = False) -> str:
-    if not force and not stale():
+def build_lib(force: bool = False, verbose: bool = False, out: str | None = None) -> str:
+    if not force and not stale() and out is None:
         return LIB
-    cmd = [_hipcc(), *FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    extra = os.environ.get("PIPELIVE_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [_hipcc(), *FLAGS, *extra, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out or LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -48,7 +49,7 @@ def build_lib(force: bool = False, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":

@@ -142,7 +142,11 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
   AttnShape sh;
   if (!attn_shape(kv, num_seqs, max_ctx, split_tokens, &sh)) return 0;
   const int G = kv->d.num_q_heads / kv->d.num_kv_heads;
-  return round_up((size_t)2 * sh.num_waves * attn_record_floats(G, kv->d.head_dim) * 4, 256);
+  size_t bytes = (size_t)2 * sh.num_waves * attn_record_floats(G, kv->d.head_dim) * 4;
+#ifdef PIPELIVE_ATTN_TRACE
+  bytes += (size_t)sh.num_waves * 64;  // development builds: 8 timestamps per wave
+#endif
+  return round_up(bytes, 256);
 }
 
 int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,

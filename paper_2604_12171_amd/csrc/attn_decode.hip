@@ -66,6 +66,18 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
   return v;
 }
 
+// Optional per-wave timestamps (development builds only): 8 slots per wave behind
+// the partial records in the workspace.
+#ifdef PIPELIVE_ATTN_TRACE
+#define TRACE_INIT() unsigned long long *trace_ = (unsigned long long *)(p.ws + 2 * (int64_t)p.num_waves * attn_record_floats(p.G, D)) + (int64_t)gw * 8
+#define TRACE(k) do { if (lane == 0) trace_[k] = wall_clock64(); } while (0)
+#define TRACE_ADD(k, v) do { if (lane == 0) trace_[k] += (v); } while (0)
+#else
+#define TRACE_INIT() do {} while (0)
+#define TRACE(k) do {} while (0)
+#define TRACE_ADD(k, v) do {} while (0)
+#endif
+
 constexpr int kTile = 32;      // tokens per tile
 constexpr int kSubTiles = 32;  // tiles whose block addresses are resolved at once
 
@@ -229,6 +241,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
   const int r = lane & 15, qg = lane >> 4;
   const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
   if (gw >= p.num_waves) return;
+  TRACE_INIT();
+  TRACE(0);
 
   // ---- total number of tiles; rows of sequences without tokens are zeroed here
   int64_t carry = 0;
@@ -272,6 +286,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
   }
 
   const int64_t rec_sz = attn_record_floats(G, D);
+  TRACE(1);
 
   int64_t t = a;
   while (t < b) {
@@ -355,6 +370,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
         pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
         kc = kn;
         vc = vn;
+        if (i == 0) TRACE(2);
       }
       {  // last tile of the batch: nothing left to prefetch
         u32x4 ph, pl;
@@ -363,6 +379,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       }
     }
 
+    TRACE(3);
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const int64_t row = (int64_t)s * p.Hq + (int64_t)g * G + r;
@@ -405,7 +422,9 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       }
     }
     t += cnt;
+    TRACE_ADD(5, 1);
   }
+  TRACE(4);
 }
 
 // Merge kernel: one wave per (sequence, KV head) pair that was cut by share
@@ -421,17 +440,18 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
   const int s = pair / Hkv, g = pair % Hkv;
   // tiles before sequence s and in total
   int64_t carry = 0, before = 0;
+  int ts = 0;
   for (int base = 0; base < S; base += 64) {
     const int ti = (base + lane < S) ? tiles_of(p.ctx[base + lane], p.max_ctx) : 0;
     const int inc = wave_inclusive_scan(ti, lane);
     if (s >= base && s < base + 64) {
       const int k = s - base;
-      before = carry + (__builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(ti, k));
+      ts = __builtin_amdgcn_readlane(ti, k);
+      before = carry + (__builtin_amdgcn_readlane(inc, k) - ts);
     }
     carry += __builtin_amdgcn_readlane(inc, 63);
   }
   const int64_t total = carry * Hkv;
-  const int ts = tiles_of(p.ctx[s], p.max_ctx);
   if (ts == 0) return;  // zero row, written by the main kernel
   const int64_t T0 = before * Hkv + (int64_t)g * ts;
   const int64_t w_first = share_wave(p, total, T0), w_last = share_wave(p, total, T0 + ts - 1);
@@ -446,7 +466,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnParams p) {
     L[j] = 0.f;
     O[j] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
-  constexpr int kChunk = 4;  // records fetched together, merged in order
+  constexpr int kChunk = NJ <= 2 ? 8 : 4;  // records fetched together, merged in order
   for (int64_t w0 = w_first; w0 <= w_last; w0 += kChunk) {
     float mw[kChunk][NJ], lw[kChunk][NJ];
     float4 ow[kChunk][NJ];
