@@ -241,7 +241,7 @@ def main():
     }
     launch_us = dec_avg * 1e3 / L
     result["roofline"] = {
-        "bound": "hbm", "kernel": "attn_decode_kernel<128,16> (+ combine), one launch per layer",
+        "bound": "hbm", "kernel": f"attn_decode_kernel<{cfg.head_dim},{cfg.block_tokens}> + attn_merge_kernel, one launch per layer",
         "achieved": round(attn_bytes_layer / (launch_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS,
         "unit": "GB/s", "frac": round(attn_bytes_layer / (launch_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
         "traffic": read_traffic(f"attn_decode_{cfg.name}"),
@@ -271,7 +271,7 @@ def main():
         bulk_patch = torch.empty(bulk_cap, dtype=torch.uint8, device="cuda")
         bulk_payload = nb * L * cfg.blk_bytes
         tc, ta = [], []
-        for it in range(6):
+        for it in range(11):
             e0, e1, e2 = ev(), ev(), ev()
             P.pipelive_kv_mark_dirty(region, bulk_ids, 0)
             e0.record()
@@ -283,9 +283,10 @@ def main():
             if it:
                 tc.append(e0.elapsed_time(e1))
                 ta.append(e1.elapsed_time(e2))
-        tcm, tam = sum(tc) / len(tc), sum(ta) / len(ta)
+        tcm, tam = sorted(tc)[len(tc) // 2], sorted(ta)[len(ta) // 2]   # medians of 10
         result["patch_bulk"] = {
             "dirty_blocks": nb, "layers": L, "payload_bytes": int(bulk_payload),
+            "timing": "median of 10",
             "collect_us": round(tcm * 1e3, 1), "collect_GBps": round(2 * bulk_payload / (tcm * 1e-3) / 1e9, 1),
             "collect_frac_of_peak": round(2 * bulk_payload / (tcm * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
             "apply_us": round(tam * 1e3, 1), "apply_GBps": round(2 * bulk_payload / (tam * 1e-3) / 1e9, 1),

@@ -72,7 +72,7 @@ def load(path: str | None = None):
     global _lib
     if _lib is not None:
         return _lib
-    path = path or _build.LIB
+    path = path or os.environ.get("PIPELIVE_LIB") or _build.LIB  # PIPELIVE_LIB: development override
     if not os.path.exists(path):
         _build.build_lib()
     L = C.CDLL(path)

@@ -44,6 +44,17 @@ int device_cu_count() {
   }
   return g_cu_count;
 }
+int copy_wgs_per_cu() {
+  static int v = 0;
+  if (v == 0) {
+    v = 16;
+    if (const char *e = getenv("PIPELIVE_COPY_WGS_PER_CU")) {  // tuning aid
+      const int x = atoi(e);
+      if (x >= 1 && x <= 64) v = x;
+    }
+  }
+  return v;
+}
 }  // namespace pipelive
 
 extern "C" {

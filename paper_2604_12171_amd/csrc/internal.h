@@ -99,5 +99,6 @@ hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const ui
 hipError_t launch_clear_status(const pipelive_kv *kv, hipStream_t st);
 
 int device_cu_count();
+int copy_wgs_per_cu();  // persistent copy workgroups launched per CU
 
 }  // namespace pipelive

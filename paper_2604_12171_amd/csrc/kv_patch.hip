@@ -186,7 +186,7 @@ hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_
   if (e != hipSuccess) return e;
   XferArgs a = make_xfer(kv, layers, nullptr);
   const int64_t max_items = (int64_t)max_blocks * layers.n * a.subs_per_block;
-  const int64_t max_grid = (int64_t)device_cu_count() * 16;
+  const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();
   const int grid = (int)(max_items < max_grid ? max_items : max_grid);
   hipLaunchKernelGGL(gather_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
   return hipGetLastError();
@@ -195,7 +195,7 @@ hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_
 hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,
                         const int32_t *dst_map, hipStream_t st) {
   XferArgs a = make_xfer(kv, layers, dst_map);
-  const int grid = device_cu_count() * 16;
+  const int grid = device_cu_count() * copy_wgs_per_cu();
   hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
   return hipGetLastError();
 }

@@ -207,7 +207,7 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
     a.move_src = move_src;
     a.move_dst = move_dst;
     a.n_items = n_moved * kv->groups * a.subs_per_block;
-    const int64_t max_grid = (int64_t)device_cu_count() * 16;
+    const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();
     const int grid = (int)(a.n_items < max_grid ? a.n_items : max_grid);
     hipLaunchKernelGGL(move_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
