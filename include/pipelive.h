@@ -176,6 +176,33 @@ size_t pipelive_kv_resize_workspace_bytes(const pipelive_kv_t *kv);
 int64_t pipelive_max_blocks(double mem_bytes, double util, int64_t layers,
                             double weight_bytes_per_layer, double block_bytes_per_layer);
 
+/* Planning arithmetic of the reconfiguration algorithm (Alg. 1; worked example
+ * in Sec. 4.1).  Host only.  GPU i holds the inclusive layer range
+ * [cur_first[i], cur_last[i]] and shall hold [tgt_first[i], tgt_last[i]]
+ * (last < first = no layers).
+ *   phase 1: C_tmp[i] = C_cur[i] U C_tgt[i];  b_shrink = min_i MaxBlocks(i, |C_tmp[i]|);
+ *            feasible = blocks_in_use <= b_shrink;  need_shrink = b_shrink < cur_blocks
+ *   phase 3: mig[k] = (src GPU, dst GPU, layer) for every layer of C_tgt[dst] \ C_cur[dst],
+ *            src = the GPU that owns the layer in C_cur (ascending dst, then layer)
+ *   phase 5: del[k] = (GPU, layer) for every layer of C_tmp[i] \ C_tgt[i];
+ *            b_new = min_i MaxBlocks(i, |C_tgt[i]|)
+ * mig holds 3*max_mig int32, del 2*max_del int32; n_mig / n_del report the
+ * full counts (PIPELIVE_E_NOSPACE if a list did not fit, PIPELIVE_E_RANGE if
+ * the target names a layer that no GPU currently holds). */
+typedef struct {
+  int32_t feasible, need_shrink;
+  int64_t b_shrink, b_new;
+  int32_t n_mig, n_del;
+} pipelive_reconfig_plan_t;
+int32_t pipelive_plan_reconfig(int32_t num_gpus, const int32_t *cur_first, const int32_t *cur_last,
+                               const int32_t *tgt_first, const int32_t *tgt_last,
+                               const double *mem_bytes, double util, double weight_bytes_per_layer,
+                               double block_bytes_per_layer, int64_t blocks_in_use,
+                               int64_t cur_blocks, pipelive_reconfig_plan_t *plan, int32_t *mig,
+                               int32_t max_mig, int32_t *del, int32_t max_del);
+/* phase 4: 1 when T_sched - T_applied[i] < tau for every destination, else 0 */
+int32_t pipelive_converged(int64_t t_sched, const int64_t *t_applied, int32_t n, int64_t tau);
+
 /* -------------------------------------------------------------------------
  * 3. Incremental KV patching (Sec. 6.1 "KV Migration with KV Patch").
  * One dirty bit per block id, shared by all layers of the region (a decode

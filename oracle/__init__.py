@@ -72,6 +72,10 @@ def lib():
                                          C.c_void_p]
         L.orc_max_blocks.restype = C.c_int64
         L.orc_max_blocks.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double]
+        L.orc_plan_reconfig.restype = C.c_int32
+        L.orc_plan_reconfig.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
+                                        C.c_double, C.c_double, C.c_int64, C.c_int64, C.c_void_p,
+                                        C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -216,3 +220,29 @@ def parse_patch_header(patch: np.ndarray) -> dict:
 def max_blocks(mem_bytes, util, layers, weight_bytes_per_layer, block_bytes_per_layer) -> int:
     return int(lib().orc_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer,
                                     block_bytes_per_layer))
+
+
+def plan_reconfig(cur_sets, tgt_sets, num_layers, mem_bytes, util, weight_bytes_per_layer,
+                  block_bytes_per_layer, blocks_in_use, cur_blocks):
+    """cur_sets / tgt_sets: one set of layer ids (0-based) per GPU.  Returns
+    (rc, dict) with the intermediate sets, M_mig as {(src, dst): set}, M_del and the scalars."""
+    n = len(cur_sets)
+    cur = np.zeros((n, num_layers), dtype=np.uint8)
+    tgt = np.zeros((n, num_layers), dtype=np.uint8)
+    for i in range(n):
+        cur[i, sorted(cur_sets[i])] = 1
+        tgt[i, sorted(tgt_sets[i])] = 1
+    tmp = np.zeros((n, num_layers), dtype=np.uint8)
+    mig = np.zeros((n, n, num_layers), dtype=np.uint8)
+    dele = np.zeros((n, num_layers), dtype=np.uint8)
+    sc = np.zeros(4, dtype=np.int64)
+    mem = np.ascontiguousarray(mem_bytes, dtype=np.float64)
+    rc = lib().orc_plan_reconfig(n, num_layers, _ptr(cur), _ptr(tgt), _ptr(mem), float(util),
+                                 float(weight_bytes_per_layer), float(block_bytes_per_layer),
+                                 int(blocks_in_use), int(cur_blocks), _ptr(tmp), _ptr(mig), _ptr(dele), _ptr(sc))
+    out = dict(
+        tmp=[set(np.nonzero(tmp[i])[0].tolist()) for i in range(n)],
+        mig={(a, b): set(np.nonzero(mig[a, b])[0].tolist()) for a in range(n) for b in range(n) if mig[a, b].any()},
+        dele=[set(np.nonzero(dele[i])[0].tolist()) for i in range(n)],
+        feasible=bool(sc[0]), need_shrink=bool(sc[1]), b_shrink=int(sc[2]), b_new=int(sc[3]))
+    return rc, out

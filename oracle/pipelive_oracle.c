@@ -340,3 +340,55 @@ int64_t orc_max_blocks(double mem_bytes, double util, int64_t layers, double wei
              ((double)layers * block_bytes_per_layer);
   return v < 0 ? 0 : (int64_t)floor(v);
 }
+
+/* ------------------------------------------------------------------ planner
+ * Alg. 1, written with explicit layer sets (one byte per layer per GPU):
+ *   C_tmp[i] = C_cur[i] U C_tgt[i]; B_shrink = min_i MaxBlocks(i, |C_tmp[i]|);
+ *   feasible iff B_used <= B_shrink; M_add(i) = C_tgt[i] \ C_cur[i];
+ *   M_mig[src][dst] gets every layer of M_add(dst) from its owner in C_cur;
+ *   M_del(i) = C_tmp[i] \ C_tgt[i]; B_new = min_i MaxBlocks(i, |C_tgt[i]|).
+ * cur/tgt: [num_gpus][num_layers] membership flags (layer ids 0..num_layers-1).
+ * Outputs: tmp [N][L] flags; mig [N][N][L] flags; del [N][L] flags;
+ * scalars[0..3] = feasible, need_shrink, B_shrink, B_new.  Returns 0, or
+ * ORC_E_RANGE when a target layer has no current owner. */
+int32_t orc_plan_reconfig(int32_t num_gpus, int32_t num_layers, const uint8_t *cur, const uint8_t *tgt,
+                          const double *mem_bytes, double util, double weight_bytes_per_layer,
+                          double block_bytes_per_layer, int64_t blocks_in_use, int64_t cur_blocks,
+                          uint8_t *tmp, uint8_t *mig, uint8_t *del, int64_t *scalars) {
+  const int N = num_gpus, L = num_layers;
+  int64_t b_shrink = -1, b_new = -1;
+  memset(mig, 0, (size_t)N * N * L);
+  for (int i = 0; i < N; ++i) {
+    int n_tmp = 0, n_tgt = 0;
+    for (int l = 0; l < L; ++l) {
+      tmp[i * L + l] = (uint8_t)(cur[i * L + l] || tgt[i * L + l]);
+      del[i * L + l] = (uint8_t)(tmp[i * L + l] && !tgt[i * L + l]);
+      n_tmp += tmp[i * L + l];
+      n_tgt += tgt[i * L + l];
+    }
+    if (n_tmp > 0) {
+      int64_t b = orc_max_blocks(mem_bytes[i], util, n_tmp, weight_bytes_per_layer, block_bytes_per_layer);
+      if (b_shrink < 0 || b < b_shrink) b_shrink = b;
+    }
+    if (n_tgt > 0) {
+      int64_t b = orc_max_blocks(mem_bytes[i], util, n_tgt, weight_bytes_per_layer, block_bytes_per_layer);
+      if (b_new < 0 || b < b_new) b_new = b;
+    }
+  }
+  if (b_shrink < 0) b_shrink = 0;
+  if (b_new < 0) b_new = 0;
+  for (int dst = 0; dst < N; ++dst)
+    for (int l = 0; l < L; ++l) {
+      if (!tgt[dst * L + l] || cur[dst * L + l]) continue; /* not in M_add(dst) */
+      int src = -1;
+      for (int j = 0; j < N; ++j)
+        if (cur[j * L + l]) src = j;
+      if (src < 0) return ORC_E_RANGE;
+      mig[((size_t)src * N + dst) * L + l] = 1;
+    }
+  scalars[0] = blocks_in_use <= b_shrink;
+  scalars[1] = b_shrink < cur_blocks;
+  scalars[2] = b_shrink;
+  scalars[3] = b_new;
+  return ORC_OK;
+}

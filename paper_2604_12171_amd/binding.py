@@ -30,7 +30,7 @@ EXPORTS = [
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
-    "pipelive_kv_clear_status", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
+    "pipelive_kv_clear_status", "pipelive_plan_reconfig", "pipelive_converged", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
 ]
 
 
@@ -55,6 +55,11 @@ class PatchHdr(C.Structure):
                 ("n_layers", C.c_uint32), ("block_bytes", C.c_uint64), ("n_acc_tokens", C.c_uint64),
                 ("payload_offset", C.c_uint64), ("max_blocks", C.c_uint32),
                 ("more_pending", C.c_uint32), ("pad", C.c_uint8 * 16)]
+
+
+class ReconfigPlan(C.Structure):
+    _fields_ = [("feasible", C.c_int32), ("need_shrink", C.c_int32), ("b_shrink", C.c_int64),
+                ("b_new", C.c_int64), ("n_mig", C.c_int32), ("n_del", C.c_int32)]
 
 
 class KVState(C.Structure):
@@ -111,6 +116,11 @@ def load(path: str | None = None):
     L.pipelive_kv_read_state.argtypes = [vp, C.POINTER(KVState), vp]
     L.pipelive_kv_clear_status.restype = i32
     L.pipelive_kv_clear_status.argtypes = [vp, vp]
+    L.pipelive_plan_reconfig.restype = i32
+    L.pipelive_plan_reconfig.argtypes = [i32, vp, vp, vp, vp, vp, C.c_double, C.c_double, C.c_double, i64,
+                                         i64, C.POINTER(ReconfigPlan), vp, i32, vp, i32]
+    L.pipelive_converged.restype = i32
+    L.pipelive_converged.argtypes = [i64, vp, i32, i64]
     L.pipelive_strerror.restype = C.c_char_p
     L.pipelive_strerror.argtypes = [i32]
     L.pipelive_last_hip_error.restype = C.c_char_p
@@ -224,6 +234,32 @@ def pipelive_kv_clear_status(kv: "KVRegion"):
 def pipelive_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer, block_bytes_per_layer) -> int:
     return int(load().pipelive_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer,
                                           block_bytes_per_layer))
+
+
+def pipelive_plan_reconfig(cur, tgt, mem_bytes, util, weight_bytes_per_layer, block_bytes_per_layer,
+                           blocks_in_use, cur_blocks):
+    """cur, tgt: lists of inclusive (first, last) layer ranges per GPU.
+    Returns (rc, ReconfigPlan, mig [(src, dst, layer)], del [(gpu, layer)])."""
+    L = load()
+    n = len(cur)
+    cf, cl = _i32_array([c[0] for c in cur]), _i32_array([c[1] for c in cur])
+    tf, tl = _i32_array([t[0] for t in tgt]), _i32_array([t[1] for t in tgt])
+    mem = (C.c_double * n)(*[float(m) for m in mem_bytes])
+    cap = sum(max(0, t[1] - t[0] + 1) for t in tgt) + sum(max(0, c[1] - c[0] + 1) for c in cur) + 1
+    mig = (C.c_int32 * (3 * cap))()
+    dele = (C.c_int32 * (2 * cap))()
+    plan = ReconfigPlan()
+    rc = L.pipelive_plan_reconfig(n, cf, cl, tf, tl, mem, float(util), float(weight_bytes_per_layer),
+                                  float(block_bytes_per_layer), int(blocks_in_use), int(cur_blocks),
+                                  C.byref(plan), mig, cap, dele, cap)
+    m = [(mig[3 * k], mig[3 * k + 1], mig[3 * k + 2]) for k in range(min(plan.n_mig, cap))] if rc in (OK, E_NOSPACE) else []
+    d = [(dele[2 * k], dele[2 * k + 1]) for k in range(min(plan.n_del, cap))] if rc in (OK, E_NOSPACE) else []
+    return rc, plan, m, d
+
+
+def pipelive_converged(t_sched, t_applied, tau) -> bool:
+    arr = (C.c_int64 * max(len(t_applied), 1))(*[int(t) for t in t_applied])
+    return bool(load().pipelive_converged(int(t_sched), arr, len(t_applied), int(tau)))
 
 
 # ---- device memory plumbing ------------------------------------------------------
