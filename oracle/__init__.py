@@ -36,7 +36,7 @@ class _KV(C.Structure):
     _fields_ = [
         ("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
         ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("stack_k", C.c_int32),
-        ("layout", C.c_int32), ("reserved", C.c_int32),
+        ("layout", C.c_int32), ("dirty_gran", C.c_int32),
         ("num_blocks", C.c_int64), ("capacity_blocks", C.c_int64),
         ("block_list", C.c_void_p), ("live_bitmap", C.c_void_p), ("dirty_bitmap", C.c_void_p),
         ("n_acc", C.c_uint64), ("t_applied", C.c_uint64),
@@ -72,6 +72,9 @@ def lib():
                                          C.c_void_p]
         L.orc_max_blocks.restype = C.c_int64
         L.orc_max_blocks.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double]
+        L.orc_kv_append.restype = C.c_int32
+        L.orc_kv_append.argtypes = [C.POINTER(_KV), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                    C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
         L.orc_plan_reconfig.restype = C.c_int32
         L.orc_plan_reconfig.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_double,
                                         C.c_double, C.c_double, C.c_int64, C.c_int64, C.c_void_p,
@@ -93,7 +96,7 @@ class HostKV:
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens,
                  num_blocks, capacity_blocks=None, layout=0, stack_k=1, arenas=3,
-                 fill_bits=0xFFFF):
+                 fill_bits=0xFFFF, dirty_gran=0):
         self.L, self.Hq, self.Hkv, self.D, self.bs = num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens
         self.layout, self.stack_k = layout, stack_k
         self.capacity = int(capacity_blocks if capacity_blocks is not None else num_blocks)
@@ -111,10 +114,13 @@ class HostKV:
                 self.arenas.append(arr)  # arena (g, a) is self.arenas[g * n_ar + a]
                 self.block_list[g, ids] = arr.ctypes.data + np.arange(len(ids), dtype=np.uint64) * np.uint64(phys_elems * 2)
         nbytes = (self.capacity + 63) // 64 * 8
+        self.dirty_gran = dirty_gran
+        self.units_per_block = block_tokens if dirty_gran else 1
+        self.unit_bytes = 2 * num_kv_heads * head_dim * 2 if dirty_gran else self.blk_bytes
         self.live = np.zeros(nbytes, dtype=np.uint8)
-        self.dirty = np.zeros(nbytes, dtype=np.uint8)
+        self.dirty = np.zeros((self.capacity * self.units_per_block + 63) // 64 * 8, dtype=np.uint8)
         self.c = _KV(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, stack_k,
-                     layout, 0, int(num_blocks), self.capacity,
+                     layout, dirty_gran, int(num_blocks), self.capacity,
                      self.block_list.ctypes.data, self.live.ctypes.data, self.dirty.ctypes.data,
                      0, 0)
 
@@ -149,7 +155,7 @@ class HostKV:
         return np.nonzero(bits)[0]
 
     def dirty_ids(self) -> np.ndarray:
-        bits = np.unpackbits(self.dirty, bitorder="little")[: self.num_blocks]
+        bits = np.unpackbits(self.dirty, bitorder="little")[: self.num_blocks * self.units_per_block]
         return np.nonzero(bits)[0]
 
     # ---- the four operations
@@ -181,6 +187,15 @@ class HostKV:
         rc = lib().orc_kv_resize(C.byref(self.c), int(new_num_blocks), tp, _ptr(rows), _ptr(strides),
                                  up, n, _ptr(remap), _ptr(result))
         return rc, remap, result
+
+    def append(self, layer, k_new, v_new, table, positions, mark=True, count_tokens=False) -> int:
+        """k_new, v_new: uint16 [S][Hkv][D]; positions int32 [S] (-1 = skip)."""
+        k = np.ascontiguousarray(k_new, dtype=np.uint16)
+        v = np.ascontiguousarray(v_new, dtype=np.uint16)
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        pos = np.ascontiguousarray(positions, dtype=np.int32)
+        return lib().orc_kv_append(C.byref(self.c), int(layer), _ptr(k), _ptr(v), _ptr(table), table.shape[1],
+                                   _ptr(pos), len(pos), int(bool(mark)), int(bool(count_tokens)))
 
     def mark_dirty(self, ids, n_tokens) -> int:
         ids = np.ascontiguousarray(ids, dtype=np.int32)
@@ -214,7 +229,7 @@ def parse_patch_header(patch: np.ndarray) -> dict:
     q = np.frombuffer(patch[:64].tobytes(), dtype=np.uint64)
     return dict(magic=int(h[0]), version=int(h[1]), n_blocks=int(h[2]), n_layers=int(h[3]),
                 block_bytes=int(q[2]), n_acc_tokens=int(q[3]), payload_offset=int(q[4]),
-                max_blocks=int(h[10]), more_pending=int(h[11]))
+                max_blocks=int(h[10]), more_pending=int(h[11]), unit_tokens=int(h[12]))
 
 
 def max_blocks(mem_bytes, util, layers, weight_bytes_per_layer, block_bytes_per_layer) -> int:

@@ -44,7 +44,8 @@ enum {
 /* A KV region on the host.  block_list holds HOST addresses. */
 typedef struct {
   int32_t num_layers, num_q_heads, num_kv_heads, head_dim;
-  int32_t block_tokens, stack_k, layout, reserved;
+  int32_t block_tokens, stack_k, layout;
+  int32_t dirty_gran;    /* dirty-tracking unit: 0 = block, 1 = token slot */
   int64_t num_blocks, capacity_blocks;
   uint64_t *block_list;  /* [ceil(L/stack_k)][capacity_blocks] */
   uint8_t *live_bitmap;  /* bit i: byte i>>3, bit i&7 */
@@ -57,7 +58,8 @@ typedef struct {
   uint32_t magic, version, n_blocks, n_layers;
   uint64_t block_bytes, n_acc_tokens, payload_offset;
   uint32_t max_blocks, more_pending;
-  uint8_t pad[16];
+  uint32_t unit_tokens; /* tokens per patch unit: block_tokens, or 1 for slot granularity */
+  uint8_t pad[12];
 } orc_patch_hdr_t;
 
 #define ORC_PATCH_MAGIC 0x564B4C50u /* bytes 'P','L','K','V' */
@@ -77,6 +79,17 @@ static double bf16_to_double(uint16_t b) {
 /* bytes of one (layer, block): K and V, all KV heads, bf16 */
 static uint64_t blk_bytes(const orc_kv_t *kv) {
   return (uint64_t)2 * kv->num_kv_heads * kv->block_tokens * kv->head_dim * 2;
+}
+
+/* dirty-tracking units: one per block, or one per token slot (the paper's own
+ * granularity: "each slot storing one token", Sec. 6.1) */
+static int64_t unit_tokens(const orc_kv_t *kv) { return kv->dirty_gran ? 1 : kv->block_tokens; }
+static int64_t num_units(const orc_kv_t *kv) {
+  return kv->num_blocks * (kv->dirty_gran ? kv->block_tokens : 1);
+}
+/* bytes one unit contributes to a patch, per layer */
+static uint64_t unit_bytes(const orc_kv_t *kv) {
+  return kv->dirty_gran ? (uint64_t)2 * kv->num_kv_heads * kv->head_dim * 2 : blk_bytes(kv);
 }
 
 static int64_t num_groups(const orc_kv_t *kv) {
@@ -195,8 +208,8 @@ int32_t orc_kv_resize(orc_kv_t *kv, int64_t new_num_blocks, int32_t **tables,
     result[0] = n_live; result[1] = 0; result[2] = B; result[3] = B;
   }
   if (new_num_blocks > kv->capacity_blocks) return ORC_E_NOSPACE;
-  for (int64_t b = 0; b < B; ++b)
-    if (get_bit(kv->dirty_bitmap, b)) return ORC_E_BUSY;
+  for (int64_t u = 0; u < num_units(kv); ++u)
+    if (get_bit(kv->dirty_bitmap, u)) return ORC_E_BUSY;
   if (n_live > new_num_blocks) return ORC_E_INFEASIBLE;
   for (int t = 0; t < num_tables; ++t)
     for (int r = 0; r < table_rows[t]; ++r)
@@ -225,10 +238,9 @@ int32_t orc_kv_resize(orc_kv_t *kv, int64_t new_num_blocks, int32_t **tables,
       ++n_moved;
     }
   } else {
-    for (int64_t b = B; b < new_num_blocks; ++b) {
-      clr_bit(kv->live_bitmap, b);
-      clr_bit(kv->dirty_bitmap, b);
-    }
+    const int64_t ut = kv->dirty_gran ? kv->block_tokens : 1;
+    for (int64_t b = B; b < new_num_blocks; ++b) clr_bit(kv->live_bitmap, b);
+    for (int64_t u = B * ut; u < new_num_blocks * ut; ++u) clr_bit(kv->dirty_bitmap, u);
   }
   for (int t = 0; t < num_tables; ++t)
     for (int r = 0; r < table_rows[t]; ++r)
@@ -248,7 +260,7 @@ int32_t orc_kv_resize(orc_kv_t *kv, int64_t new_num_blocks, int32_t **tables,
 int32_t orc_kv_mark_dirty(orc_kv_t *kv, const int32_t *ids, int32_t n, int64_t n_tokens) {
   if (!kv || n < 0 || n_tokens < 0) return ORC_E_INVAL;
   for (int i = 0; i < n; ++i)
-    if (ids[i] < 0 || ids[i] >= kv->num_blocks) return ORC_E_RANGE;
+    if (ids[i] < 0 || ids[i] >= num_units(kv)) return ORC_E_RANGE;
   for (int i = 0; i < n; ++i) set_bit(kv->dirty_bitmap, ids[i]);
   kv->n_acc += (uint64_t)n_tokens;
   return ORC_OK;
@@ -259,9 +271,9 @@ static uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 /* largest number of blocks a patch buffer of `capacity` bytes can carry */
 int64_t orc_patch_max_blocks(const orc_kv_t *kv, int32_t n_layers, uint64_t capacity) {
   if (capacity < 64 + 256) return 0;
-  uint64_t per = 4 + (uint64_t)n_layers * blk_bytes(kv);
+  uint64_t per = 4 + (uint64_t)n_layers * unit_bytes(kv);
   uint64_t mb = (capacity - 64 - 256) / per;
-  if (mb > (uint64_t)kv->num_blocks) mb = (uint64_t)kv->num_blocks;
+  if (mb > (uint64_t)num_units(kv)) mb = (uint64_t)num_units(kv);
   return (int64_t)mb;
 }
 
@@ -276,26 +288,40 @@ int32_t orc_kv_patch_collect(orc_kv_t *kv, const int32_t *layers, int32_t n_laye
     if (layers[i] < 0 || layers[i] >= kv->num_layers) return ORC_E_RANGE;
   int64_t max_blocks = orc_patch_max_blocks(kv, n_layers, capacity);
   if (max_blocks <= 0) return ORC_E_NOSPACE;
-  const uint64_t bb = blk_bytes(kv);
+  const uint64_t bb = unit_bytes(kv);
   orc_patch_hdr_t h;
   memset(&h, 0, sizeof h);
   h.magic = ORC_PATCH_MAGIC;
   h.version = ORC_PATCH_VERSION;
   h.n_layers = (uint32_t)n_layers;
   h.block_bytes = bb;
+  h.unit_tokens = (uint32_t)unit_tokens(kv);
   h.max_blocks = (uint32_t)max_blocks;
   h.payload_offset = round_up(64 + 4 * (uint64_t)max_blocks, 256);
   int32_t *ids = (int32_t *)(patch + 64);
   uint8_t *payload = patch + h.payload_offset;
   uint32_t n = 0;
   int more = 0;
-  for (int64_t b = 0; b < kv->num_blocks; ++b) {
-    if (!get_bit(kv->dirty_bitmap, b)) continue;
+  for (int64_t u = 0; u < num_units(kv); ++u) {
+    if (!get_bit(kv->dirty_bitmap, u)) continue;
     if ((int64_t)n == max_blocks) { more = 1; break; }
-    clr_bit(kv->dirty_bitmap, b);
-    ids[n] = (int32_t)b;
-    for (int i = 0; i < n_layers; ++i)
-      memcpy(payload + ((uint64_t)n * n_layers + i) * bb, layer_block(kv, layers[i], b), bb);
+    clr_bit(kv->dirty_bitmap, u);
+    ids[n] = (int32_t)u;
+    for (int i = 0; i < n_layers; ++i) {
+      uint8_t *dst = payload + ((uint64_t)n * n_layers + i) * bb;
+      if (!kv->dirty_gran) {
+        memcpy(dst, layer_block(kv, layers[i], u), bb);
+      } else { /* one token: K[Hkv][D] then V[Hkv][D], gathered out of the block layout */
+        const uint16_t *blk = (const uint16_t *)layer_block(kv, layers[i], u / kv->block_tokens);
+        uint16_t *o = (uint16_t *)dst;
+        const int t = (int)(u % kv->block_tokens), Hkv = kv->num_kv_heads, D = kv->head_dim;
+        for (int g = 0; g < Hkv; ++g)
+          for (int d = 0; d < D; ++d) {
+            o[g * D + d] = blk[k_elem(kv, g, t, d)];
+            o[Hkv * D + g * D + d] = blk[v_elem(kv, g, t, d)];
+          }
+      }
+    }
     ++n;
   }
   h.n_blocks = n;
@@ -313,22 +339,76 @@ int32_t orc_kv_patch_apply(orc_kv_t *dst, const int32_t *dst_layers, int32_t n_l
   orc_patch_hdr_t h;
   memcpy(&h, patch, sizeof h);
   if (h.magic != ORC_PATCH_MAGIC || h.version != ORC_PATCH_VERSION) return ORC_E_INVAL;
-  if (h.n_layers != (uint32_t)n_layers || h.block_bytes != blk_bytes(dst)) return ORC_E_INVAL;
+  if (h.n_layers != (uint32_t)n_layers || h.block_bytes != unit_bytes(dst)) return ORC_E_INVAL;
+  if (h.unit_tokens != (uint32_t)unit_tokens(dst)) return ORC_E_INVAL;
   for (int i = 0; i < n_layers; ++i)
     if (dst_layers[i] < 0 || dst_layers[i] >= dst->num_layers) return ORC_E_RANGE;
   const int32_t *ids = (const int32_t *)(patch + 64);
+  const int64_t upb = dst->dirty_gran ? dst->block_tokens : 1; /* units per block */
   for (uint32_t r = 0; r < h.n_blocks; ++r) {
-    int64_t id = dst_map ? dst_map[ids[r]] : ids[r];
-    if (id < 0 || id >= dst->num_blocks) return ORC_E_RANGE;
+    int64_t blk_id = ids[r] / upb;
+    if (dst_map) blk_id = dst_map[blk_id];
+    if (blk_id < 0 || blk_id >= dst->num_blocks) return ORC_E_RANGE;
   }
   const uint8_t *payload = patch + h.payload_offset;
   for (uint32_t r = 0; r < h.n_blocks; ++r) {
-    int64_t id = dst_map ? dst_map[ids[r]] : ids[r];
-    for (int i = 0; i < n_layers; ++i)
-      memcpy(layer_block(dst, dst_layers[i], id),
-             payload + ((uint64_t)r * n_layers + i) * h.block_bytes, h.block_bytes);
+    int64_t blk_id = ids[r] / upb;
+    if (dst_map) blk_id = dst_map[blk_id];
+    for (int i = 0; i < n_layers; ++i) {
+      const uint8_t *src = payload + ((uint64_t)r * n_layers + i) * h.block_bytes;
+      if (!dst->dirty_gran) {
+        memcpy(layer_block(dst, dst_layers[i], blk_id), src, h.block_bytes);
+      } else {
+        uint16_t *blk = (uint16_t *)layer_block(dst, dst_layers[i], blk_id);
+        const uint16_t *o = (const uint16_t *)src;
+        const int t = (int)(ids[r] % upb), Hkv = dst->num_kv_heads, D = dst->head_dim;
+        for (int g = 0; g < Hkv; ++g)
+          for (int d = 0; d < D; ++d) {
+            blk[k_elem(dst, g, t, d)] = o[g * D + d];
+            blk[v_elem(dst, g, t, d)] = o[Hkv * D + g * D + d];
+          }
+      }
+    }
   }
   dst->t_applied += h.n_acc_tokens;
+  return ORC_OK;
+}
+
+/* -------------------------------------------------------------------- append
+ * The write side of a decode step for one layer (Sec. 6.1: after each step the
+ * inference worker marks the newly written slots dirty): token `positions[s]`
+ * of sequence s gets K/V k_new[s], v_new[s] ([Hkv][D] each) in block
+ * table[s][pos / bs], slot pos % bs.  positions[s] < 0 skips the sequence.
+ * mark != 0 sets the dirty bit of the written unit; count_tokens != 0 adds the
+ * number of written tokens to n_acc (done for one layer per step: n^(t) counts
+ * tokens, not layer writes). */
+int32_t orc_kv_append(orc_kv_t *kv, int32_t layer, const uint16_t *k_new, const uint16_t *v_new,
+                      const int32_t *table, int32_t table_stride, const int32_t *positions,
+                      int32_t num_seqs, int32_t mark, int32_t count_tokens) {
+  if (!kv || layer < 0 || layer >= kv->num_layers) return ORC_E_INVAL;
+  const int Hkv = kv->num_kv_heads, D = kv->head_dim, bs = kv->block_tokens;
+  for (int s = 0; s < num_seqs; ++s) {
+    if (positions[s] < 0) continue;
+    if (positions[s] / bs >= table_stride) return ORC_E_INVAL;
+    int32_t id = table[(int64_t)s * table_stride + positions[s] / bs];
+    if (id < 0 || id >= kv->num_blocks) return ORC_E_RANGE;
+  }
+  uint64_t written = 0;
+  for (int s = 0; s < num_seqs; ++s) {
+    const int pos = positions[s];
+    if (pos < 0) continue;
+    const int32_t id = table[(int64_t)s * table_stride + pos / bs];
+    const int t = pos % bs;
+    uint16_t *blk = (uint16_t *)layer_block(kv, layer, id);
+    for (int g = 0; g < Hkv; ++g)
+      for (int d = 0; d < D; ++d) {
+        blk[k_elem(kv, g, t, d)] = k_new[((int64_t)s * Hkv + g) * D + d];
+        blk[v_elem(kv, g, t, d)] = v_new[((int64_t)s * Hkv + g) * D + d];
+      }
+    if (mark) set_bit(kv->dirty_bitmap, kv->dirty_gran ? (int64_t)id * bs + t : id);
+    ++written;
+  }
+  if (count_tokens) kv->n_acc += written;
   return ORC_OK;
 }
 
