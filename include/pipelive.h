@@ -51,6 +51,8 @@ extern "C" {
 #define PIPELIVE_E_HIP (-6)        /* HIP runtime error, see pipelive_last_hip_error() */
 
 #define PIPELIVE_LAYOUT_D8 0
+#define PIPELIVE_DIRTY_BLOCK 0
+#define PIPELIVE_DIRTY_SLOT 1
 #define PIPELIVE_DTYPE_BF16 0
 #define PIPELIVE_OUT_F32 0
 #define PIPELIVE_OUT_BF16 1
@@ -71,20 +73,27 @@ typedef struct {
   int32_t stack_k;         /* layers per physical block (Sec. 5.2); 1 = one pool per layer */
   int32_t dtype;           /* PIPELIVE_DTYPE_BF16 */
   int32_t in_block_layout; /* PIPELIVE_LAYOUT_D8 */
+  int32_t dirty_granularity; /* PIPELIVE_DIRTY_BLOCK: one dirty bit per block id;
+                                PIPELIVE_DIRTY_SLOT: one per token slot (unit id = block id * bs + slot),
+                                the paper's own granularity (Sec. 6.1) */
+  int32_t reserved0;       /* 0 */
   int64_t num_blocks;      /* B: valid ids are 0 .. B-1 */
   int64_t capacity_blocks; /* entries per group in block_list, B <= capacity < 2^31 */
   const uint64_t *block_list; /* DEVICE [ceil(L/stack_k)][capacity]: block addresses, 256-B aligned */
   uint8_t *live_bitmap;    /* DEVICE, pipelive_bitmap_bytes(capacity): bit i = byte i>>3, bit i&7;
                               maintained by the caller's block manager, updated by resize */
-  uint8_t *dirty_bitmap;   /* DEVICE, same size and bit order; maintained by the library; zeroed by the caller at start */
-  void *dev_state;         /* DEVICE, pipelive_kv_state_bytes(capacity) bytes, 256-B aligned,
+  uint8_t *dirty_bitmap;   /* DEVICE, pipelive_bitmap_bytes(U) with U = pipelive_kv_dirty_units(capacity, bs,
+                              granularity), same bit order; maintained by the library; zeroed by the caller at start */
+  void *dev_state;         /* DEVICE, pipelive_kv_state_bytes(U) bytes, 256-B aligned,
                               zeroed by the caller before pipelive_kv_create */
 } pipelive_kv_desc_t;
 
-/* bytes of one bitmap for `capacity_blocks` ids (a whole number of 64-bit words) */
-size_t pipelive_bitmap_bytes(int64_t capacity_blocks);
-/* bytes of the per-region device state (counters, status, drain snapshot) */
-size_t pipelive_kv_state_bytes(int64_t capacity_blocks);
+/* bytes of one bitmap of `n_bits` bits (a whole number of 64-bit words) */
+size_t pipelive_bitmap_bytes(int64_t n_bits);
+/* dirty-tracking units of a region: capacity (block granularity) or capacity * block_tokens */
+int64_t pipelive_kv_dirty_units(int64_t capacity_blocks, int32_t block_tokens, int32_t granularity);
+/* bytes of the per-region device state (counters, status, drain snapshot) for `dirty_units` units */
+size_t pipelive_kv_state_bytes(int64_t dirty_units);
 
 /* Create / destroy the host-side handle.  No device work. */
 int32_t pipelive_kv_create(const pipelive_kv_desc_t *desc, pipelive_kv_t **out);
@@ -205,12 +214,29 @@ int32_t pipelive_converged(int64_t t_sched, const int64_t *t_applied, int32_t n,
 
 /* -------------------------------------------------------------------------
  * 3. Incremental KV patching (Sec. 6.1 "KV Migration with KV Patch").
- * One dirty bit per block id, shared by all layers of the region (a decode
- * step writes the same slot in every layer).
+ * One dirty bit per *unit*, shared by all layers of the region (a decode step
+ * writes the same slot in every layer).  A unit is a block
+ * (PIPELIVE_DIRTY_BLOCK) or one token slot (PIPELIVE_DIRTY_SLOT, unit id =
+ * block id * bs + slot); a unit's patch entry is the block's bytes verbatim,
+ * or the token's K[Hkv][D] followed by its V[Hkv][D] (bf16, gathered out of
+ * the in-block layout).
  *
- * mark_dirty: B[id] <- 1 for the n ids in block_ids (DEVICE int32), and
- * n_acc += n_tokens (the tokens scheduled in that step).  Asynchronous.
+ * append: the write side of a decode step for one layer.  Token
+ * positions[s] (>= 0; < 0 skips the sequence) of sequence s receives
+ * k_new[s], v_new[s] (DEVICE bf16 [num_seqs][Hkv][D], 16-B aligned) in block
+ * block_table[s][pos / bs], slot pos % bs.  mark != 0 sets the dirty bit of
+ * the written unit; count_tokens != 0 adds the number of written tokens to
+ * n_acc (pass it for one layer per step: n(t) counts tokens, not layer
+ * writes).  A bad block id or a position beyond the table row sets the status
+ * word and writes nothing for that sequence.  Asynchronous.
  */
+int32_t pipelive_kv_append(pipelive_kv_t *kv, int32_t layer, const void *k_new, const void *v_new,
+                           const int32_t *block_table, int32_t table_stride,
+                           const int32_t *positions, int32_t num_seqs, int32_t mark,
+                           int32_t count_tokens, void *stream);
+
+/* mark_dirty: B[id] <- 1 for the n unit ids in ids (DEVICE int32), and
+ * n_acc += n_tokens (the tokens scheduled in that step).  Asynchronous. */
 int32_t pipelive_kv_mark_dirty(pipelive_kv_t *kv, const int32_t *block_ids, int32_t n,
                                int64_t n_tokens, void *stream);
 
@@ -224,11 +250,12 @@ typedef struct {
   uint64_t payload_offset; /* round_up(64 + 4 * max_blocks, 256) */
   uint32_t max_blocks;     /* capacity of the id list */
   uint32_t more_pending;   /* 1 if dirty bits were left behind */
-  uint8_t pad[16];
+  uint32_t unit_tokens;    /* tokens per unit: bs (block granularity) or 1 (slot granularity) */
+  uint8_t pad[12];
 } pipelive_patch_hdr_t;
 
-/* number of blocks a patch buffer of `capacity` bytes can carry:
- * min(B, floor((capacity - 320) / (4 + n_layers * blk))) */
+/* number of units a patch buffer of `capacity` bytes can carry:
+ * min(units of the region, floor((capacity - 320) / (4 + n_layers * unit_bytes))) */
 int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, size_t capacity);
 
 /* collect: atomically take the dirty set D (ascending ids, at most
@@ -256,7 +283,9 @@ int32_t pipelive_kv_patch_collect(pipelive_kv_t *src, const int32_t *layers, int
  * the entry.  Asynchronous.
  *
  * dst_layers     HOST int32 [n_layers]
- * dst_block_map  DEVICE int32 indexed by source id, or NULL
+ * dst_block_map  DEVICE int32 indexed by source *block* id, or NULL (a slot keeps
+ *                its position inside the mapped block); source and target must
+ *                have the same dirty granularity
  */
 int32_t pipelive_kv_patch_apply(pipelive_kv_t *dst, const int32_t *dst_layers, int32_t n_layers,
                                 const void *patch_buf, const int32_t *dst_block_map, void *stream);

@@ -19,13 +19,14 @@ from . import build as _build
 
 OK, E_INVAL, E_INFEASIBLE, E_NOSPACE, E_BUSY, E_RANGE, E_HIP = 0, -1, -2, -3, -4, -5, -6
 LAYOUT_D8 = 0
+DIRTY_BLOCK, DIRTY_SLOT = 0, 1
 OUT_F32, OUT_BF16 = 0, 1
 MAX_PATCH_LAYERS = 128
 MAX_TABLES = 8
 PATCH_MAGIC = 0x564B4C50
 
 EXPORTS = [
-    "pipelive_bitmap_bytes", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
+    "pipelive_bitmap_bytes", "pipelive_kv_dirty_units", "pipelive_kv_append", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
     "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_workspace_bytes",
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
@@ -39,6 +40,7 @@ class KVDesc(C.Structure):
         ("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
         ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("stack_k", C.c_int32),
         ("dtype", C.c_int32), ("in_block_layout", C.c_int32),
+        ("dirty_granularity", C.c_int32), ("reserved0", C.c_int32),
         ("num_blocks", C.c_int64), ("capacity_blocks", C.c_int64),
         ("block_list", C.c_void_p), ("live_bitmap", C.c_void_p), ("dirty_bitmap", C.c_void_p),
         ("dev_state", C.c_void_p),
@@ -54,7 +56,7 @@ class PatchHdr(C.Structure):
     _fields_ = [("magic", C.c_uint32), ("version", C.c_uint32), ("n_blocks", C.c_uint32),
                 ("n_layers", C.c_uint32), ("block_bytes", C.c_uint64), ("n_acc_tokens", C.c_uint64),
                 ("payload_offset", C.c_uint64), ("max_blocks", C.c_uint32),
-                ("more_pending", C.c_uint32), ("pad", C.c_uint8 * 16)]
+                ("more_pending", C.c_uint32), ("unit_tokens", C.c_uint32), ("pad", C.c_uint8 * 12)]
 
 
 class ReconfigPlan(C.Structure):
@@ -84,6 +86,10 @@ def load(path: str | None = None):
     vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     L.pipelive_bitmap_bytes.restype = sz
     L.pipelive_bitmap_bytes.argtypes = [i64]
+    L.pipelive_kv_dirty_units.restype = i64
+    L.pipelive_kv_dirty_units.argtypes = [i64, i32, i32]
+    L.pipelive_kv_append.restype = i32
+    L.pipelive_kv_append.argtypes = [vp, i32, vp, vp, vp, i32, vp, i32, i32, i32, vp]
     L.pipelive_kv_state_bytes.restype = sz
     L.pipelive_kv_state_bytes.argtypes = [i64]
     L.pipelive_kv_create.restype = i32
@@ -194,6 +200,15 @@ def pipelive_kv_resize(kv: "KVRegion", new_num_blocks, tables=(), used=(), remap
     return rc, res
 
 
+def pipelive_kv_append(kv: "KVRegion", layer, k_new, v_new, block_table, positions, mark=True,
+                       count_tokens=False, check=True):
+    """k_new, v_new bf16 [S][Hkv][D]; positions int32 [S] (-1 skips a sequence)."""
+    rc = load().pipelive_kv_append(kv.handle, int(layer), _p(k_new), _p(v_new), _p(block_table),
+                                   int(block_table.shape[1]), _p(positions), int(positions.numel()),
+                                   int(bool(mark)), int(bool(count_tokens)), _stream())
+    return _check(rc) if check else rc
+
+
 def pipelive_kv_mark_dirty(kv: "KVRegion", block_ids, n_tokens, check=True):
     L = load()
     rc = L.pipelive_kv_mark_dirty(kv.handle, _p(block_ids), int(block_ids.numel()), int(n_tokens),
@@ -273,7 +288,8 @@ class KVRegion:
     memory (the rest of the block list is null and must not be used)."""
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
-                 capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda"):
+                 capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda",
+                 dirty_granularity=DIRTY_BLOCK):
         L = load()
         if not torch.cuda.is_available():
             raise RuntimeError("pipelive needs a GPU: no CPU fallback exists")
@@ -298,12 +314,15 @@ class KVRegion:
                 bl[g, a::n_ar] = t.data_ptr() + torch.arange(cnt, dtype=torch.int64) * (phys * 2)
         self.block_list = bl.to(self.device)
         nb = L.pipelive_bitmap_bytes(self.capacity)
+        self.dirty_granularity = dirty_granularity
+        self.units_per_block = block_tokens if dirty_granularity == DIRTY_SLOT else 1
+        self.unit_bytes = 2 * num_kv_heads * head_dim * 2 if dirty_granularity == DIRTY_SLOT else self.blk_bytes
+        units = L.pipelive_kv_dirty_units(self.capacity, block_tokens, dirty_granularity)
         self.live = torch.zeros(nb, dtype=torch.uint8, device=self.device)
-        self.dirty = torch.zeros(nb, dtype=torch.uint8, device=self.device)
-        self.state = torch.zeros(L.pipelive_kv_state_bytes(self.capacity), dtype=torch.uint8,
-                                 device=self.device)
+        self.dirty = torch.zeros(L.pipelive_bitmap_bytes(units), dtype=torch.uint8, device=self.device)
+        self.state = torch.zeros(L.pipelive_kv_state_bytes(units), dtype=torch.uint8, device=self.device)
         d = KVDesc(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, stack_k, 0,
-                   LAYOUT_D8, int(num_blocks), self.capacity, self.block_list.data_ptr(),
+                   LAYOUT_D8, dirty_granularity, 0, int(num_blocks), self.capacity, self.block_list.data_ptr(),
                    self.live.data_ptr(), self.dirty.data_ptr(), self.state.data_ptr())
         h = C.c_void_p()
         torch.cuda.synchronize()

@@ -59,12 +59,16 @@ int copy_wgs_per_cu() {
 
 extern "C" {
 
-size_t pipelive_bitmap_bytes(int64_t capacity_blocks) {
-  return capacity_blocks <= 0 ? 8 : (size_t)((capacity_blocks + 63) / 64 * 8);
+size_t pipelive_bitmap_bytes(int64_t n_bits) {
+  return n_bits <= 0 ? 8 : (size_t)((n_bits + 63) / 64 * 8);
 }
 
-size_t pipelive_kv_state_bytes(int64_t capacity_blocks) {
-  return kSnapOffset + round_up(pipelive_bitmap_bytes(capacity_blocks), 256);
+int64_t pipelive_kv_dirty_units(int64_t capacity_blocks, int32_t block_tokens, int32_t granularity) {
+  return granularity == PIPELIVE_DIRTY_SLOT ? capacity_blocks * block_tokens : capacity_blocks;
+}
+
+size_t pipelive_kv_state_bytes(int64_t dirty_units) {
+  return kSnapOffset + round_up(pipelive_bitmap_bytes(dirty_units), 256);
 }
 
 int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
@@ -77,6 +81,10 @@ int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
   if (d->block_tokens != 16 && d->block_tokens != 32) return PIPELIVE_E_INVAL;
   if (d->stack_k < 1 || d->dtype != PIPELIVE_DTYPE_BF16) return PIPELIVE_E_INVAL;
   if (d->in_block_layout != PIPELIVE_LAYOUT_D8) return PIPELIVE_E_INVAL;
+  if (d->dirty_granularity != PIPELIVE_DIRTY_BLOCK && d->dirty_granularity != PIPELIVE_DIRTY_SLOT)
+    return PIPELIVE_E_INVAL;
+  if (pipelive_kv_dirty_units(d->capacity_blocks, d->block_tokens, d->dirty_granularity) >= (1ll << 31))
+    return PIPELIVE_E_INVAL;
   if (d->num_blocks < 0 || d->capacity_blocks < d->num_blocks) return PIPELIVE_E_INVAL;
   if (d->capacity_blocks >= (1ll << 31)) return PIPELIVE_E_INVAL;
   if (!d->block_list || !d->live_bitmap || !d->dirty_bitmap || !d->dev_state)
@@ -90,6 +98,10 @@ int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
   kv->groups = (d->num_layers + d->stack_k - 1) / d->stack_k;
   kv->blk_bytes = (uint64_t)2 * d->num_kv_heads * d->block_tokens * d->head_dim * 2;
   kv->phys_bytes = kv->blk_bytes * (uint64_t)d->stack_k;
+  kv->units_per_block = d->dirty_granularity == PIPELIVE_DIRTY_SLOT ? d->block_tokens : 1;
+  kv->unit_bytes = d->dirty_granularity == PIPELIVE_DIRTY_SLOT
+                       ? (uint64_t)2 * d->num_kv_heads * d->head_dim * 2
+                       : kv->blk_bytes;
   kv->pinned = nullptr;
   hipError_t e = hipHostMalloc((void **)&kv->pinned, sizeof(HostPinned), hipHostMallocDefault);
   if (e != hipSuccess) {
@@ -292,11 +304,26 @@ int32_t pipelive_kv_mark_dirty(pipelive_kv_t *kv, const int32_t *block_ids, int3
   return PIPELIVE_OK;
 }
 
+int32_t pipelive_kv_append(pipelive_kv_t *kv, int32_t layer, const void *k_new, const void *v_new,
+                           const int32_t *block_table, int32_t table_stride,
+                           const int32_t *positions, int32_t num_seqs, int32_t mark,
+                           int32_t count_tokens, void *stream) {
+  if (!kv || !k_new || !v_new || !block_table || !positions) return PIPELIVE_E_INVAL;
+  if (layer < 0 || layer >= kv->d.num_layers) return PIPELIVE_E_RANGE;
+  if (num_seqs < 0 || table_stride <= 0 || !aligned(k_new, 16) || !aligned(v_new, 16))
+    return PIPELIVE_E_INVAL;
+  if (num_seqs == 0) return PIPELIVE_OK;
+  HIP_TRY(launch_append(kv, layer, (const uint16_t *)k_new, (const uint16_t *)v_new, block_table,
+                        table_stride, positions, num_seqs, mark, count_tokens, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
 int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, size_t capacity) {
   if (!kv || n_layers <= 0 || capacity < 64 + 256) return 0;
-  const uint64_t per = 4 + (uint64_t)n_layers * kv->blk_bytes;
+  const uint64_t per = 4 + (uint64_t)n_layers * kv->unit_bytes;
   uint64_t mb = (capacity - 64 - 256) / per;
-  if (mb > (uint64_t)kv->d.num_blocks) mb = (uint64_t)kv->d.num_blocks;
+  const uint64_t units = (uint64_t)(kv->d.num_blocks * kv->units_per_block);
+  if (mb > units) mb = units;
   return (int64_t)mb;
 }
 

@@ -30,6 +30,8 @@ struct pipelive_kv {
   int64_t groups;
   uint64_t blk_bytes;   // one (layer, block)
   uint64_t phys_bytes;  // one physical block = stack_k * blk_bytes
+  int64_t units_per_block;  // dirty-tracking units per block: 1 or block_tokens
+  uint64_t unit_bytes;      // patch bytes of one unit per layer
   pipelive::HostPinned *pinned;
 };
 
@@ -92,6 +94,10 @@ struct LayerList {
 };
 hipError_t launch_mark(const pipelive_kv *kv, const int32_t *ids, int32_t n, int64_t n_tokens,
                        hipStream_t st);
+hipError_t launch_append(const pipelive_kv *kv, int32_t layer, const uint16_t *k_new,
+                         const uint16_t *v_new, const int32_t *table, int32_t table_stride,
+                         const int32_t *positions, int32_t num_seqs, int32_t mark,
+                         int32_t count_tokens, hipStream_t st);
 hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
                           uint32_t max_blocks, uint64_t payload_offset, hipStream_t st);
 hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,

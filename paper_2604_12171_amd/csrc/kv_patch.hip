@@ -2,7 +2,13 @@
 // dirty bitmap, atomic drain, gather of the dirty blocks into a contiguous
 // patch, scatter-apply on the target, and the n_acc / T_applied counters.
 //
-// mark    : atomicOr of one bit per written block; n_acc += n_tokens.
+// A dirty-tracking unit is a block or, at slot granularity, one token slot
+// (unit id = block id * bs + slot); a slot's patch entry is the token's
+// K[Hkv][D] then V[Hkv][D], gathered out of the in-block layout.
+//
+// append  : write one new token per sequence into its slot (K as 16-byte
+//           d-slices, V element-wise), mark the written unit, count tokens.
+// mark    : atomicOr of one bit per written unit; n_acc += n_tokens.
 // drain   : one workgroup swaps every bitmap word with zero (atomicExch, so a
 //           concurrent mark is either in this snapshot or stays for the next
 //           drain), prefix-sums the popcounts, writes the ascending id list
@@ -37,7 +43,8 @@ __global__ void mark_kernel(u64 *dirty, int64_t B, const int32_t *ids, int32_t n
 __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t B, u64 *snap,
                                                              DevState *st, uint8_t *patch,
                                                              uint32_t max_blocks, uint32_t n_layers,
-                                                             u64 block_bytes, u64 payload_offset) {
+                                                             u64 block_bytes, u64 payload_offset,
+                                                             uint32_t unit_tokens) {
   __shared__ uint32_t sh[17];
   const int64_t nwords = (B + 63) / 64;
   const int64_t per = (nwords + kScanThreads - 1) / kScanThreads;
@@ -77,7 +84,8 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
     h.n_acc_tokens = h.more_pending ? 0ull : atomicExch(&st->n_acc, 0ull);
     h.payload_offset = payload_offset;
     h.max_blocks = max_blocks;
-    for (int i = 0; i < 16; ++i) h.pad[i] = 0;
+    h.unit_tokens = unit_tokens;
+    for (int i = 0; i < 12; ++i) h.pad[i] = 0;
     *(pipelive_patch_hdr_t *)patch = h;
   }
 }
@@ -86,6 +94,7 @@ struct XferArgs {
   const uint64_t *block_list;
   int64_t capacity, num_blocks;
   uint32_t stack_k, blk_bytes, sub_bytes, subs_per_block;
+  uint32_t Hkv, D, bs, unit_tokens;
   LayerList layers;
   const int32_t *dst_map;
   DevState *st;
@@ -119,7 +128,7 @@ __global__ __launch_bounds__(kCopyThreads) void scatter_kernel(XferArgs a, const
   const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
   const uint32_t nl = a.layers.n;
   if (h->magic != PIPELIVE_PATCH_MAGIC || h->version != PIPELIVE_PATCH_VERSION ||
-      h->n_layers != nl || h->block_bytes != a.blk_bytes) {
+      h->n_layers != nl || h->block_bytes != a.blk_bytes || h->unit_tokens != a.unit_tokens) {
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
     return;
   }
@@ -149,6 +158,120 @@ __global__ __launch_bounds__(kCopyThreads) void scatter_kernel(XferArgs a, const
   }
 }
 
+// ---- slot granularity: one token per unit -------------------------------------
+// Copy token `t` of a layer's block between the in-block layout
+// (K[Hkv][D/8][bs][8], V[Hkv][D][bs]) and a token-major record K[Hkv][D] | V[Hkv][D].
+// to_record = true gathers block -> record, false scatters record -> block.
+template <bool to_record>
+__device__ __forceinline__ void wg_copy_token(char *blk, char *rec, uint32_t t, uint32_t Hkv,
+                                              uint32_t D, uint32_t bs) {
+  const uint32_t n_chunks = Hkv * D / 8;  // K: 16-byte d-slices
+  for (uint32_t c = threadIdx.x; c < n_chunks; c += blockDim.x) {
+    u32x4 *in_blk = (u32x4 *)(blk + ((uint64_t)c * bs + t) * 16);
+    u32x4 *in_rec = (u32x4 *)(rec + (uint64_t)c * 16);
+    if (to_record) *in_rec = *in_blk;
+    else *in_blk = *in_rec;
+  }
+  const uint32_t n_el = Hkv * D;  // V: one bf16 per (head, d), bs apart in the block
+  uint16_t *vblk = (uint16_t *)(blk + (uint64_t)Hkv * bs * D * 2);
+  uint16_t *vrec = (uint16_t *)(rec + (uint64_t)n_el * 2);
+  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) {
+    if (to_record) vrec[e] = vblk[(uint64_t)e * bs + t];
+    else vblk[(uint64_t)e * bs + t] = vrec[e];
+  }
+}
+
+__global__ __launch_bounds__(kCopyThreads) void gather_slots_kernel(XferArgs a, uint8_t *patch) {
+  const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
+  const int32_t *ids = (const int32_t *)(patch + 64);
+  char *payload = (char *)patch + h->payload_offset;
+  const uint32_t nl = a.layers.n;
+  const int64_t n_items = (int64_t)h->n_blocks * nl;
+  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const uint32_t i = (uint32_t)(item % nl);
+    const int64_t r = item / nl;
+    const int32_t layer = a.layers.layer[i];
+    const int32_t u = ids[r];
+    char *blk = (char *)a.block_list[(int64_t)(layer / a.stack_k) * a.capacity + u / a.bs] +
+                (uint64_t)(layer % a.stack_k) * ((uint64_t)2 * a.Hkv * a.bs * a.D * 2);
+    wg_copy_token<true>(blk, payload + (uint64_t)item * a.blk_bytes, u % a.bs, a.Hkv, a.D, a.bs);
+  }
+}
+
+__global__ __launch_bounds__(kCopyThreads) void scatter_slots_kernel(XferArgs a, const uint8_t *patch) {
+  const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
+  const uint32_t nl = a.layers.n;
+  if (h->magic != PIPELIVE_PATCH_MAGIC || h->version != PIPELIVE_PATCH_VERSION ||
+      h->n_layers != nl || h->block_bytes != a.blk_bytes || h->unit_tokens != a.unit_tokens) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
+    return;
+  }
+  const int32_t *ids = (const int32_t *)(patch + 64);
+  const char *payload = (const char *)patch + h->payload_offset;
+  if (blockIdx.x == 0 && threadIdx.x == 0 && h->n_acc_tokens)
+    atomicAdd(&a.st->t_applied, (u64)h->n_acc_tokens);
+  const int64_t n_items = (int64_t)h->n_blocks * nl;
+  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const uint32_t i = (uint32_t)(item % nl);
+    const int64_t r = item / nl;
+    const int32_t layer = a.layers.layer[i];
+    const int32_t u = ids[r];
+    int64_t id = u / a.bs;
+    if (a.dst_map) id = a.dst_map[id];
+    if (id < 0 || id >= a.num_blocks) {  // uniform over the workgroup
+      if (threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_RANGE);
+      continue;
+    }
+    char *blk = (char *)a.block_list[(int64_t)(layer / a.stack_k) * a.capacity + id] +
+                (uint64_t)(layer % a.stack_k) * ((uint64_t)2 * a.Hkv * a.bs * a.D * 2);
+    wg_copy_token<false>(blk, (char *)payload + (uint64_t)item * a.blk_bytes, u % a.bs, a.Hkv, a.D, a.bs);
+  }
+}
+
+struct AppendArgs {
+  const uint64_t *block_list;  // the layer's group row
+  uint64_t layer_off;
+  int64_t num_blocks;
+  const uint16_t *k_new, *v_new;
+  const int32_t *table, *positions;
+  int32_t table_stride;
+  uint32_t Hkv, D, bs, units_per_block;
+  int32_t mark, count_tokens;
+  u64 *dirty;
+  DevState *st;
+};
+
+// one workgroup per sequence: the new token's K and V of one layer
+__global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
+  const int s = blockIdx.x;
+  const int pos = a.positions[s];
+  if (pos < 0) return;
+  if (pos / (int)a.bs >= a.table_stride) {
+    if (threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
+    return;
+  }
+  const int32_t id = a.table[(int64_t)s * a.table_stride + pos / (int)a.bs];
+  if (id < 0 || id >= a.num_blocks) {
+    if (threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_RANGE);
+    return;
+  }
+  const uint32_t t = (uint32_t)pos % a.bs;
+  char *blk = (char *)a.block_list[id] + a.layer_off;
+  const uint32_t n_el = a.Hkv * a.D;
+  const uint16_t *k = a.k_new + (int64_t)s * n_el, *v = a.v_new + (int64_t)s * n_el;
+  for (uint32_t c = threadIdx.x; c < n_el / 8; c += blockDim.x)
+    *(u32x4 *)(blk + ((uint64_t)c * a.bs + t) * 16) = *(const u32x4 *)(k + (uint64_t)c * 8);
+  uint16_t *vblk = (uint16_t *)(blk + (uint64_t)a.Hkv * a.bs * a.D * 2);
+  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) vblk[(uint64_t)e * a.bs + t] = v[e];
+  if (threadIdx.x == 0) {
+    if (a.mark) {
+      const int64_t u = a.units_per_block > 1 ? (int64_t)id * a.bs + t : id;
+      atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
+    }
+    if (a.count_tokens) atomicAdd(&a.st->n_acc, 1ull);
+  }
+}
+
 __global__ void clear_status_kernel(DevState *st) { st->status = 0; }
 
 XferArgs make_xfer(const pipelive_kv *kv, const LayerList &layers, const int32_t *dst_map) {
@@ -157,7 +280,11 @@ XferArgs make_xfer(const pipelive_kv *kv, const LayerList &layers, const int32_t
   a.capacity = kv->d.capacity_blocks;
   a.num_blocks = kv->d.num_blocks;
   a.stack_k = (uint32_t)kv->d.stack_k;
-  a.blk_bytes = (uint32_t)kv->blk_bytes;
+  a.blk_bytes = (uint32_t)kv->unit_bytes;  // bytes of one patch entry
+  a.Hkv = (uint32_t)kv->d.num_kv_heads;
+  a.D = (uint32_t)kv->d.head_dim;
+  a.bs = (uint32_t)kv->d.block_tokens;
+  a.unit_tokens = kv->units_per_block > 1 ? 1u : a.bs;
   a.sub_bytes = kCopyChunk;
   a.subs_per_block = (a.blk_bytes + a.sub_bytes - 1) / a.sub_bytes;
   a.layers = layers;
@@ -173,22 +300,50 @@ hipError_t launch_mark(const pipelive_kv *kv, const int32_t *ids, int32_t n, int
   const int threads = 256;
   const int grid = n > 0 ? (n + threads - 1) / threads : 1;
   hipLaunchKernelGGL(mark_kernel, dim3(grid), dim3(threads), 0, st, (u64 *)kv->d.dirty_bitmap,
-                     kv->d.num_blocks, ids, n, (u64)n_tokens, dev_state(kv));
+                     kv->d.num_blocks * kv->units_per_block, ids, n, (u64)n_tokens, dev_state(kv));
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const pipelive_kv *kv, int32_t layer, const uint16_t *k_new,
+                         const uint16_t *v_new, const int32_t *table, int32_t table_stride,
+                         const int32_t *positions, int32_t num_seqs, int32_t mark,
+                         int32_t count_tokens, hipStream_t st) {
+  AppendArgs a;
+  a.block_list = kv->d.block_list + (int64_t)(layer / kv->d.stack_k) * kv->d.capacity_blocks;
+  a.layer_off = (uint64_t)(layer % kv->d.stack_k) * kv->blk_bytes;
+  a.num_blocks = kv->d.num_blocks;
+  a.k_new = k_new;
+  a.v_new = v_new;
+  a.table = table;
+  a.positions = positions;
+  a.table_stride = table_stride;
+  a.Hkv = (uint32_t)kv->d.num_kv_heads;
+  a.D = (uint32_t)kv->d.head_dim;
+  a.bs = (uint32_t)kv->d.block_tokens;
+  a.units_per_block = (uint32_t)kv->units_per_block;
+  a.mark = mark;
+  a.count_tokens = count_tokens;
+  a.dirty = (u64 *)kv->d.dirty_bitmap;
+  a.st = dev_state(kv);
+  hipLaunchKernelGGL(append_kernel, dim3(num_seqs), dim3(kCopyThreads), 0, st, a);
   return hipGetLastError();
 }
 
 hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
                           uint32_t max_blocks, uint64_t payload_offset, hipStream_t st) {
+  const bool slots = kv->units_per_block > 1;
   hipLaunchKernelGGL(drain_kernel, dim3(1), dim3(kScanThreads), 0, st, (u64 *)kv->d.dirty_bitmap,
-                     kv->d.num_blocks, snap_words(kv), dev_state(kv), patch, max_blocks,
-                     (uint32_t)layers.n, (u64)kv->blk_bytes, (u64)payload_offset);
+                     kv->d.num_blocks * kv->units_per_block, snap_words(kv), dev_state(kv), patch,
+                     max_blocks, (uint32_t)layers.n, (u64)kv->unit_bytes, (u64)payload_offset,
+                     slots ? 1u : (uint32_t)kv->d.block_tokens);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   XferArgs a = make_xfer(kv, layers, nullptr);
-  const int64_t max_items = (int64_t)max_blocks * layers.n * a.subs_per_block;
+  const int64_t max_items = (int64_t)max_blocks * layers.n * (slots ? 1 : a.subs_per_block);
   const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();
   const int grid = (int)(max_items < max_grid ? max_items : max_grid);
-  hipLaunchKernelGGL(gather_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
+  if (slots) hipLaunchKernelGGL(gather_slots_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
+  else hipLaunchKernelGGL(gather_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
   return hipGetLastError();
 }
 
@@ -196,7 +351,10 @@ hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const ui
                         const int32_t *dst_map, hipStream_t st) {
   XferArgs a = make_xfer(kv, layers, dst_map);
   const int grid = device_cu_count() * copy_wgs_per_cu();
-  hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
+  if (kv->units_per_block > 1)
+    hipLaunchKernelGGL(scatter_slots_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
+  else
+    hipLaunchKernelGGL(scatter_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);
   return hipGetLastError();
 }
 

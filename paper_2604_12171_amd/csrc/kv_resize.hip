@@ -32,8 +32,8 @@ __device__ __forceinline__ u64 range_mask(int64_t word, int64_t lo, int64_t hi) 
 }
 
 __global__ __launch_bounds__(kScanThreads) void resize_plan_kernel(
-    const u64 *live, const u64 *dirty, int64_t B, int64_t B_new, ResizePlanOut *plan,
-    int32_t *move_src, int32_t *move_dst) {
+    const u64 *live, const u64 *dirty, int64_t n_dirty_units, int64_t B, int64_t B_new,
+    ResizePlanOut *plan, int32_t *move_src, int32_t *move_dst) {
   __shared__ uint32_t sh[17];
   __shared__ uint32_t sh_live[kScanThreads / 64], sh_dirty[kScanThreads / 64];
   const int64_t nwords = (B + 63) / 64;
@@ -47,8 +47,9 @@ __global__ __launch_bounds__(kScanThreads) void resize_plan_kernel(
     cL += __popcll(lv);
     cT += __popcll(lv & range_mask(w, B_new, B));
     cF += __popcll(~lv & range_mask(w, 0, B_new < B ? B_new : B));
-    anyd |= (dirty[w] & in) != 0;
   }
+  for (int64_t w = threadIdx.x; w < (n_dirty_units + 63) / 64; w += kScanThreads)
+    anyd |= (dirty[w] & range_mask(w, 0, n_dirty_units)) != 0;
   uint32_t totT, totF;
   const uint32_t exT = wg_exclusive_scan(cT, sh, &totT);
   const uint32_t exF = wg_exclusive_scan(cF, sh, &totF);
@@ -163,14 +164,13 @@ __global__ void live_update_kernel(u64 *live, int64_t n_moved, const int32_t *mo
 }
 
 // grow: ids [B, B_new) become valid and are neither live nor dirty
-__global__ void grow_kernel(u64 *live, u64 *dirty, int64_t B, int64_t B_new, int32_t *remap) {
+__global__ void grow_kernel(u64 *live, u64 *dirty, int64_t B, int64_t B_new, int64_t upb,
+                            int32_t *remap) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t w_lo = B / 64, w_hi = (B_new + 63) / 64;
-  if (i < w_hi - w_lo) {
-    const u64 m = ~range_mask(w_lo + i, B, B_new);
-    atomicAnd(&live[w_lo + i], m);
-    atomicAnd(&dirty[w_lo + i], m);
-  }
+  if (i < w_hi - w_lo) atomicAnd(&live[w_lo + i], ~range_mask(w_lo + i, B, B_new));
+  const int64_t d_lo = B * upb / 64, d_hi = (B_new * upb + 63) / 64;  // dirty units of the new ids
+  if (i < d_hi - d_lo) atomicAnd(&dirty[d_lo + i], ~range_mask(d_lo + i, B * upb, B_new * upb));
   if (remap && i < B) remap[i] = ((live[i >> 6] >> (i & 63)) & 1ull) ? (int32_t)i : -1;
 }
 
@@ -179,8 +179,8 @@ __global__ void grow_kernel(u64 *live, u64 *dirty, int64_t B, int64_t B_new, int
 hipError_t launch_resize_plan(const pipelive_kv *kv, int64_t B, int64_t B_new, ResizePlanOut *plan,
                               int32_t *move_src, int32_t *move_dst, hipStream_t st) {
   hipLaunchKernelGGL(resize_plan_kernel, dim3(1), dim3(kScanThreads), 0, st,
-                     (const u64 *)kv->d.live_bitmap, (const u64 *)kv->d.dirty_bitmap, B, B_new,
-                     plan, move_src, move_dst);
+                     (const u64 *)kv->d.live_bitmap, (const u64 *)kv->d.dirty_bitmap,
+                     B * kv->units_per_block, B, B_new, plan, move_src, move_dst);
   return hipGetLastError();
 }
 
@@ -237,11 +237,12 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
 
 hipError_t launch_grow(const pipelive_kv *kv, int64_t B, int64_t B_new, int32_t *remap,
                        hipStream_t st) {
-  const int64_t words = (B_new + 63) / 64 - B / 64;
+  const int64_t upb = kv->units_per_block;
+  const int64_t words = (B_new * upb + 63) / 64 - B * upb / 64 + 1;
   const int64_t n = words > B ? words : B;
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(grow_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     (u64 *)kv->d.live_bitmap, (u64 *)kv->d.dirty_bitmap, B, B_new, remap);
+                     (u64 *)kv->d.live_bitmap, (u64 *)kv->d.dirty_bitmap, B, B_new, upb, remap);
   return hipGetLastError();
 }
 

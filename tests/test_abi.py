@@ -38,9 +38,9 @@ def test_host_only_helpers():
 def test_create_rejects_bad_descriptors_without_a_gpu():
     lib = P.load()
     h = C.c_void_p()
-    d = P.binding.KVDesc(2, 4, 2, 64, 16, 1, 0, 0, 8, 8, None, None, None, None)
+    d = P.binding.KVDesc(2, 4, 2, 64, 16, 1, 0, 0, 0, 0, 8, 8, None, None, None, None)
     assert lib.pipelive_kv_create(C.byref(d), C.byref(h)) == P.E_INVAL   # null device pointers
-    d = P.binding.KVDesc(2, 4, 3, 64, 16, 1, 0, 0, 8, 8, 256, 256, 256, 256)
+    d = P.binding.KVDesc(2, 4, 3, 64, 16, 1, 0, 0, 0, 0, 8, 8, 256, 256, 256, 256)
     assert lib.pipelive_kv_create(C.byref(d), C.byref(h)) == P.E_INVAL   # Hq % Hkv != 0
-    d = P.binding.KVDesc(2, 4, 2, 64, 16, 1, 0, 0, 9, 8, 256, 256, 256, 256)
+    d = P.binding.KVDesc(2, 4, 2, 64, 16, 1, 0, 0, 0, 0, 9, 8, 256, 256, 256, 256)
     assert lib.pipelive_kv_create(C.byref(d), C.byref(h)) == P.E_INVAL   # B > capacity
