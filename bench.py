@@ -296,6 +296,41 @@ def main():
             raise RuntimeError("device status word set during the bench")
         del bulk_patch
 
+    # ---------------- steady-state decode at slot granularity (the paper's own unit): every layer
+    # appends one token per sequence, the written slots are drained and applied
+    if not args.decode_only:
+        sreg = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B,
+                          dirty_granularity=P.binding.DIRTY_SLOT, share_pool_of=region)
+        stgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live,
+                          dirty_granularity=P.binding.DIRTY_SLOT, share_pool_of=target)
+        knew = torch.zeros((S, cfg.num_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+        room = batch.ctx_lens < batch.used.astype(np.int64) * cfg.block_tokens   # a free slot in the last block
+        pos_d = torch.from_numpy(np.where(room, batch.ctx_lens, -1).astype(np.int32)).cuda()
+        n_tok = int(room.sum())
+        spatch = torch.empty(64 + 256 + S * (4 + L * cfg.token_bytes) + 4096, dtype=torch.uint8, device="cuda")
+        tapp, tcol, tapl = [], [], []
+        for it in range(11):
+            e0, e1, e2, e3 = ev(), ev(), ev(), ev()
+            e0.record()
+            for l in range(L):
+                P.pipelive_kv_append(sreg, l, knew, knew, table_d, pos_d, mark=True, count_tokens=(l == 0))
+            e1.record()
+            P.pipelive_kv_patch_collect(sreg, all_layers, spatch)
+            e2.record()
+            P.pipelive_kv_patch_apply(stgt, all_layers, spatch, dst_block_map=dst_map)
+            e3.record()
+            torch.cuda.synchronize()
+            if it:
+                tapp.append(e0.elapsed_time(e1)); tcol.append(e1.elapsed_time(e2)); tapl.append(e2.elapsed_time(e3))
+        med = lambda v: sorted(v)[len(v) // 2]
+        if P.pipelive_kv_read_state(stgt).t_applied != 11 * n_tok or P.pipelive_kv_read_state(sreg).status != 0:
+            raise RuntimeError("slot-granular cycle lost tokens")
+        result["slot_patch"] = {
+            "tokens_per_step": n_tok, "layers": L, "payload_bytes": n_tok * L * cfg.token_bytes,
+            "append_all_layers_us": round(med(tapp) * 1e3, 1), "collect_us": round(med(tcol) * 1e3, 1),
+            "apply_us": round(med(tapl) * 1e3, 1),
+            "note": "block-granular patch of the same step carries %d bytes" % (n_dirty * L * cfg.blk_bytes)}
+
     # ---------------- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         import oracle

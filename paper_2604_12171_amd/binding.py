@@ -289,7 +289,7 @@ class KVRegion:
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
                  capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda",
-                 dirty_granularity=DIRTY_BLOCK):
+                 dirty_granularity=DIRTY_BLOCK, share_pool_of: "KVRegion | None" = None):
         L = load()
         if not torch.cuda.is_available():
             raise RuntimeError("pipelive needs a GPU: no CPU fallback exists")
@@ -301,18 +301,26 @@ class KVRegion:
         self.groups = (num_layers + stack_k - 1) // stack_k
         self.device = torch.device(device)
         phys = self.blk_elems * stack_k
-        self._n_ar = n_ar = max(1, min(arenas, self.capacity))
-        self.arenas = []
-        bl = torch.zeros((self.groups, self.capacity), dtype=torch.int64)
-        for g in range(self.groups):
-            for a in range(n_ar):
-                cnt = len(range(a, self.capacity, n_ar))
-                t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
-                if fill_bits is not None:
-                    t.fill_(fill_bits - 65536 if fill_bits >= 32768 else fill_bits)
-                self.arenas.append(t)
-                bl[g, a::n_ar] = t.data_ptr() + torch.arange(cnt, dtype=torch.int64) * (phys * 2)
-        self.block_list = bl.to(self.device)
+        if share_pool_of is not None:
+            # a second handle over the same physical blocks (own dirty bitmap and state),
+            # e.g. to track the same pool at another dirty granularity
+            o = share_pool_of
+            assert (o.L_, o.Hkv, o.D, o.bs, o.stack_k, o.capacity) == (num_layers, num_kv_heads, head_dim,
+                                                                      block_tokens, stack_k, self.capacity)
+            self._n_ar, self.arenas, self.block_list = o._n_ar, o.arenas, o.block_list
+        else:
+            self._n_ar = n_ar = max(1, min(arenas, self.capacity))
+            self.arenas = []
+            bl = torch.zeros((self.groups, self.capacity), dtype=torch.int64)
+            for g in range(self.groups):
+                for a in range(n_ar):
+                    cnt = len(range(a, self.capacity, n_ar))
+                    t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
+                    if fill_bits is not None:
+                        t.fill_(fill_bits - 65536 if fill_bits >= 32768 else fill_bits)
+                    self.arenas.append(t)
+                    bl[g, a::n_ar] = t.data_ptr() + torch.arange(cnt, dtype=torch.int64) * (phys * 2)
+            self.block_list = bl.to(self.device)
         nb = L.pipelive_bitmap_bytes(self.capacity)
         self.dirty_granularity = dirty_granularity
         self.units_per_block = block_tokens if dirty_granularity == DIRTY_SLOT else 1

@@ -68,7 +68,9 @@ int64_t pipelive_kv_dirty_units(int64_t capacity_blocks, int32_t block_tokens, i
 }
 
 size_t pipelive_kv_state_bytes(int64_t dirty_units) {
-  return kSnapOffset + round_up(pipelive_bitmap_bytes(dirty_units), 256);
+  // counters | drain snapshot words | per-workgroup counts of the multi-kernel drain
+  const size_t words = pipelive_bitmap_bytes(dirty_units) / 8;
+  return kSnapOffset + round_up(words * 8 + (words / 256 + 2) * 4, 256);
 }
 
 int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {

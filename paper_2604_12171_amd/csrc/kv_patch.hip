@@ -90,6 +90,98 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
   }
 }
 
+// ---- drain of a large bitmap in three small kernels (used above kDrainOneWgWords
+// words, e.g. slot granularity on a big pool): count per workgroup, scan the
+// workgroup counts, emit.  Same result as drain_kernel.
+constexpr int kDrainThreads = 256;
+constexpr int64_t kDrainOneWgWords = 4096;
+
+__global__ __launch_bounds__(kDrainThreads) void drain_count_kernel(u64 *dirty, int64_t nwords, u64 *snap,
+                                                                    uint32_t *wg_count) {
+  __shared__ uint32_t sh[kDrainThreads / 64];
+  const int64_t w = (int64_t)blockIdx.x * kDrainThreads + threadIdx.x;
+  u64 v = 0;
+  if (w < nwords) {
+    v = dirty[w];
+    if (v) v = atomicExch(&dirty[w], 0ull);
+    snap[w] = v;
+  }
+  uint32_t c = __popcll(v);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint32_t t = 0;
+    for (int i = 0; i < kDrainThreads / 64; ++i) t += sh[i];
+    wg_count[blockIdx.x] = t;
+  }
+}
+
+// exclusive scan of the workgroup counts (in place) and the patch header
+__global__ __launch_bounds__(kScanThreads) void drain_scan_kernel(uint32_t *wg_count, int64_t n_wg, DevState *st,
+                                                                  uint8_t *patch, uint32_t max_blocks,
+                                                                  uint32_t n_layers, u64 block_bytes,
+                                                                  u64 payload_offset, uint32_t unit_tokens) {
+  __shared__ uint32_t sh[17];
+  uint32_t carry = 0;
+  for (int64_t base = 0; base < n_wg; base += kScanThreads) {
+    const int64_t i = base + threadIdx.x;
+    const uint32_t c = i < n_wg ? wg_count[i] : 0;
+    uint32_t tot;
+    const uint32_t ex = wg_exclusive_scan(c, sh, &tot);
+    if (i < n_wg) wg_count[i] = carry + ex;
+    carry += tot;
+  }
+  if (threadIdx.x == 0) {
+    const uint32_t total = carry;
+    pipelive_patch_hdr_t h;
+    h.magic = PIPELIVE_PATCH_MAGIC;
+    h.version = PIPELIVE_PATCH_VERSION;
+    h.n_blocks = total < max_blocks ? total : max_blocks;
+    h.n_layers = n_layers;
+    h.block_bytes = block_bytes;
+    h.more_pending = total > max_blocks ? 1u : 0u;
+    h.n_acc_tokens = h.more_pending ? 0ull : atomicExch(&st->n_acc, 0ull);
+    h.payload_offset = payload_offset;
+    h.max_blocks = max_blocks;
+    h.unit_tokens = unit_tokens;
+    for (int i = 0; i < 12; ++i) h.pad[i] = 0;
+    *(pipelive_patch_hdr_t *)patch = h;
+  }
+}
+
+__global__ __launch_bounds__(kDrainThreads) void drain_emit_kernel(u64 *dirty, int64_t nwords, const u64 *snap,
+                                                                   const uint32_t *wg_offset, uint8_t *patch,
+                                                                   uint32_t max_blocks) {
+  __shared__ uint32_t sh[kDrainThreads / 64];
+  const int64_t w = (int64_t)blockIdx.x * kDrainThreads + threadIdx.x;
+  u64 v = w < nwords ? snap[w] : 0;
+  const uint32_t c = __popcll(v);
+  // exclusive prefix inside the workgroup: wave scan, then the 4 wave totals
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  uint32_t inc = c;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  if (lane == 63) sh[wv] = inc;
+  __syncthreads();
+  uint32_t rank = wg_offset[blockIdx.x] + inc - c;
+  for (int i = 0; i < wv; ++i) rank += sh[i];
+  int32_t *ids = (int32_t *)(patch + 64);
+  u64 back = 0;
+  while (v) {
+    const int b = __ffsll((long long)v) - 1;
+    if (rank < max_blocks) ids[rank] = (int32_t)(w * 64 + b);
+    else back |= 1ull << b;
+    ++rank;
+    v &= v - 1;
+  }
+  if (back) atomicOr(&dirty[w], back);
+}
+
 struct XferArgs {
   const uint64_t *block_list;
   int64_t capacity, num_blocks;
@@ -332,12 +424,30 @@ hipError_t launch_append(const pipelive_kv *kv, int32_t layer, const uint16_t *k
 hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
                           uint32_t max_blocks, uint64_t payload_offset, hipStream_t st) {
   const bool slots = kv->units_per_block > 1;
-  hipLaunchKernelGGL(drain_kernel, dim3(1), dim3(kScanThreads), 0, st, (u64 *)kv->d.dirty_bitmap,
-                     kv->d.num_blocks * kv->units_per_block, snap_words(kv), dev_state(kv), patch,
-                     max_blocks, (uint32_t)layers.n, (u64)kv->unit_bytes, (u64)payload_offset,
-                     slots ? 1u : (uint32_t)kv->d.block_tokens);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  const int64_t n_units = kv->d.num_blocks * kv->units_per_block;
+  const int64_t nwords = (n_units + 63) / 64;
+  const uint32_t unit_tokens = slots ? 1u : (uint32_t)kv->d.block_tokens;
+  hipError_t e;
+  if (nwords <= kDrainOneWgWords) {
+    hipLaunchKernelGGL(drain_kernel, dim3(1), dim3(kScanThreads), 0, st, (u64 *)kv->d.dirty_bitmap,
+                       n_units, snap_words(kv), dev_state(kv), patch, max_blocks, (uint32_t)layers.n,
+                       (u64)kv->unit_bytes, (u64)payload_offset, unit_tokens);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  } else {
+    const int64_t n_wg = (nwords + kDrainThreads - 1) / kDrainThreads;
+    uint32_t *wg_count = (uint32_t *)(snap_words(kv) + nwords);  // behind the snapshot words
+    hipLaunchKernelGGL(drain_count_kernel, dim3((unsigned)n_wg), dim3(kDrainThreads), 0, st,
+                       (u64 *)kv->d.dirty_bitmap, nwords, snap_words(kv), wg_count);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(drain_scan_kernel, dim3(1), dim3(kScanThreads), 0, st, wg_count, n_wg,
+                       dev_state(kv), patch, max_blocks, (uint32_t)layers.n, (u64)kv->unit_bytes,
+                       (u64)payload_offset, unit_tokens);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL(drain_emit_kernel, dim3((unsigned)n_wg), dim3(kDrainThreads), 0, st,
+                       (u64 *)kv->d.dirty_bitmap, nwords, (const u64 *)snap_words(kv),
+                       (const uint32_t *)wg_count, patch, max_blocks);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   XferArgs a = make_xfer(kv, layers, nullptr);
   const int64_t max_items = (int64_t)max_blocks * layers.n * (slots ? 1 : a.subs_per_block);
   const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();

@@ -146,3 +146,37 @@ def test_slot_mode_resize_busy_grow_and_errors():
     P.pipelive_kv_patch_collect(dev, [0], patch)
     P.pipelive_kv_patch_apply(blk_tgt, [0], patch)
     assert P.pipelive_kv_read_state(blk_tgt).status == P.E_INVAL
+
+
+def test_large_slot_bitmap_uses_the_multi_kernel_drain():
+    """320 000 slot bits (5 000 words): ids, clipping, put-back and counters must
+    equal the oracle's single sweep."""
+    rng = np.random.default_rng(77)
+    B, bs = 20000, 16
+    host, dev = _pair(1, 1, 1, 1, 64, bs, B, arenas=2)
+    units = B * bs
+    marks = np.unique(rng.integers(0, units, 6000)).astype(np.int32)
+    marks = np.concatenate([marks, [0, 63, 64, units - 1]]).astype(np.int32)
+    # give the marked slots' blocks recognisable content on both sides
+    blocks = np.unique(marks // bs)
+    data = rng.integers(0, 30000, (len(blocks), host.blk_elems), dtype=np.uint16)
+    for b, row in zip(blocks, data):
+        host.block(0, int(b))[:] = row
+    dev.write_blocks(0, blocks, torch.from_numpy(data.view(np.int16)).cuda())
+    assert host.mark_dirty(marks, 123) == oracle.OK
+    P.pipelive_kv_mark_dirty(dev, torch.from_numpy(marks).cuda(), 123)
+    cap = 64 + 256 + 2500 * (4 + host.unit_bytes)
+    patch_h = np.zeros(cap, dtype=np.uint8)
+    patch_d = torch.zeros(cap, dtype=torch.uint8, device="cuda")
+    drains, seen = 0, []
+    while True:
+        assert host.patch_collect([0], patch_h) == oracle.OK
+        P.pipelive_kv_patch_collect(dev, [0], patch_d)
+        h = _cmp_patch(host, patch_h, patch_d, 1)
+        assert np.array_equal(bitmap_ids(dev.dirty, units), host.dirty_ids())
+        assert P.pipelive_kv_read_state(dev).n_acc == host.n_acc
+        seen += np.frombuffer(patch_h[64:64 + 4 * h["n_blocks"]].tobytes(), dtype=np.int32).tolist()
+        drains += 1
+        if not h["more_pending"]:
+            break
+    assert drains == 3 and seen == sorted(set(marks.tolist()))
