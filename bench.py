@@ -111,6 +111,10 @@ def main():
     ctx = pin.draw_ctx_lens(cfg, seed)
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = args.pool_blocks or int(0.85 * free // (L * cfg.blk_bytes))
+    if not args.decode_only and not args.pool_blocks:
+        # the migration target, the patch buffers and the oracle sample must fit beside the pool
+        extra = n_live * L * cfg.blk_bytes * (1.0 + args.bulk_fraction + 0.05) + (8 << 30)
+        B = min(B, int((free - extra) // (L * cfg.blk_bytes)))
     B = max(B, int(math.ceil(n_live * 1.3)))
     region = None
     while region is None:
@@ -145,8 +149,8 @@ def main():
     # migration target: a compact region reached through a block map
     Lm = min(args.mig_layers, L)
     mig_layers = list(range(L - Lm, L))
-    target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
-                        n_live, arenas=2)
+    target = None if args.decode_only else P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
+                                                      cfg.block_tokens, n_live, arenas=2)
     dst_map = torch.full((B,), -1, dtype=torch.int32)
     dst_map[torch.from_numpy(batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
     dst_map = dst_map.cuda()

@@ -136,12 +136,21 @@ static bool attn_shape(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ct
   const int64_t upper = (int64_t)num_seqs * kv->d.num_kv_heads * ((max_ctx + 31) / 32);
   if (split_tokens == 0) {
     // equal shares over exactly the waves the device keeps resident
+    // One wave per SIMD: measured on MI355X, 768-1024 waves with one 16 KiB tile in
+    // flight and one being computed (24-32 MB outstanding) saturate HBM; more waves
+    // only lengthen the queues that every dependent access (block table, block
+    // list, partial records) then has to wait in.
     int wpc = attn_waves_per_cu(kv->d.head_dim, kv->d.block_tokens);
+    if (wpc > 4) wpc = 4;
     if (const char *e = getenv("PIPELIVE_ATTN_WAVES_PER_CU")) {  // tuning aid
       const int v = atoi(e);
-      if (v >= 1 && v <= wpc) wpc = v;
+      if (v >= 1 && v <= 16) wpc = v;
     }
-    const int64_t resident = (int64_t)device_cu_count() * wpc;
+    int64_t resident = (int64_t)device_cu_count() * wpc;
+    if (const char *e = getenv("PIPELIVE_ATTN_WAVES")) {  // tuning aid: absolute number of waves
+      const int v = atoi(e);
+      if (v >= 4 && v <= 65536) resident = v;
+    }
     int64_t nw = upper < resident ? upper : resident;
     out->num_waves = (int32_t)(nw < 1 ? 1 : nw);
     out->tiles_per_wave = 0;
