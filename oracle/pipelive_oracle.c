@@ -81,8 +81,8 @@ static uint64_t blk_bytes(const orc_kv_t *kv) {
   return (uint64_t)2 * kv->num_kv_heads * kv->block_tokens * kv->head_dim * 2;
 }
 
-/* dirty-tracking units: one per block, or one per token slot (the paper's own
- * granularity: "each slot storing one token", Sec. 6.1) */
+/* dirty-tracking units: one per block, or one per token slot (the granularity
+ * of the paper's bitmap, Sec. 6.1) */
 static int64_t unit_tokens(const orc_kv_t *kv) { return kv->dirty_gran ? 1 : kv->block_tokens; }
 static int64_t num_units(const orc_kv_t *kv) {
   return kv->num_blocks * (kv->dirty_gran ? kv->block_tokens : 1);
@@ -375,8 +375,8 @@ int32_t orc_kv_patch_apply(orc_kv_t *dst, const int32_t *dst_layers, int32_t n_l
 }
 
 /* -------------------------------------------------------------------- append
- * The write side of a decode step for one layer (Sec. 6.1: after each step the
- * inference worker marks the newly written slots dirty): token `positions[s]`
+ * The write side of a decode step for one layer (Sec. 6.1: the inference side
+ * flags the slots a step wrote): token `positions[s]`
  * of sequence s gets K/V k_new[s], v_new[s] ([Hkv][D] each) in block
  * table[s][pos / bs], slot pos % bs.  positions[s] < 0 skips the sequence.
  * mark != 0 sets the dirty bit of the written unit; count_tokens != 0 adds the

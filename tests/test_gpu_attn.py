@@ -142,3 +142,45 @@ def test_argument_errors():
     assert P.pipelive_paged_attn_decode(dev, 0, q, out, t, c, split_tokens=64, workspace=ws[:16], check=False) == P.E_NOSPACE
     with pytest.raises(P.PipeliveError):
         P.KVRegion(2, 4, 2, 96, 16, 8)                     # head_dim not supported
+
+
+def test_many_sequences_multi_chunk_scan_and_all_empty():
+    """More than 64 sequences (the wave-wide prefix sums run in several chunks),
+    many of them empty or a single token; then a batch with no tokens at all."""
+    rng = np.random.default_rng(5)
+    ctx = rng.integers(0, 90, 200).astype(np.int32)
+    ctx[::7] = 0
+    ctx[3::11] = 1
+    ctx[150] = 1500
+    cfg = _cfg(16, 2, 128, 16, ctx.tolist())
+    batch = _batch(cfg, ctx.tolist())
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    for split in (0, 32, 512):
+        got = _run(cfg, batch, dev, 1, split).cpu().numpy()
+        ref = host.attn_decode(1, pin.q_bits(cfg, SEED, 1), batch.table, batch.ctx_lens, nthreads=8)
+        assert np.isfinite(got).all()
+        ma, rl = attn_errors(got, ref)
+        assert ma <= MAX_ABS and rl <= REL_L2, (split, ma, rl)
+        assert (got[ctx == 0] == 0).all()
+    zero = pin.Batch(cfg, SEED, batch.num_blocks, np.zeros_like(batch.ctx_lens), batch.table, batch.used, batch.live_ids)
+    out = _run(cfg, zero, dev, 0, 0).cpu().numpy()
+    assert (out == 0).all()
+    assert P.pipelive_kv_read_state(dev).status == 0
+
+
+def test_context_longer_than_max_ctx_is_truncated_and_flagged():
+    ctx = [300, 40]
+    cfg = _cfg(4, 2, 64, 16, ctx)
+    batch = _batch(cfg, ctx)
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    q = torch.from_numpy(pin.q_bits(cfg, SEED, 0).view(np.int16)).cuda().view(torch.bfloat16)
+    out = torch.full((2, 4, 64), float("nan"), dtype=torch.float32, device="cuda")
+    P.pipelive_paged_attn_decode(dev, 0, q, out, torch.from_numpy(batch.table).cuda(),
+                                 torch.from_numpy(batch.ctx_lens).cuda(), max_ctx=128)
+    torch.cuda.synchronize()
+    assert P.pipelive_kv_read_state(dev).status == P.E_RANGE
+    ref = host.attn_decode(0, pin.q_bits(cfg, SEED, 0), batch.table, np.array([128, 40], dtype=np.int32))
+    ma, rl = attn_errors(out.cpu().numpy(), ref)
+    assert ma <= MAX_ABS and rl <= REL_L2           # sequence 0 is attended over its first 128 tokens only
