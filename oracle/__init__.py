@@ -72,6 +72,9 @@ def lib():
                                          C.c_void_p]
         L.orc_max_blocks.restype = C.c_int64
         L.orc_max_blocks.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double]
+        L.orc_paged_attn_prefill.restype = C.c_int32
+        L.orc_paged_attn_prefill.argtypes = [C.POINTER(_KV), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                             C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_int32]
         L.orc_kv_append.restype = C.c_int32
         L.orc_kv_append.argtypes = [C.POINTER(_KV), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                     C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
@@ -167,6 +170,19 @@ class HostKV:
         out = np.empty((S, self.Hq, self.D), dtype=np.float32)
         rc = lib().orc_paged_attn_decode(C.byref(self.c), layer, _ptr(q), _ptr(out), _ptr(table),
                                          table.shape[1], _ptr(ctx), S, float(scale), nthreads)
+        if rc != OK:
+            raise OracleError(rc)
+        return out
+
+    def attn_prefill(self, layer, q_bits, table, ctx_lens, q_offsets, scale=0.0, nthreads=1) -> np.ndarray:
+        """q_bits uint16 [total_q][Hq][D]; q_offsets int32 [S+1]; returns float32 [total_q][Hq][D]."""
+        q = np.ascontiguousarray(q_bits, dtype=np.uint16)
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        ctx = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        qo = np.ascontiguousarray(q_offsets, dtype=np.int32)
+        out = np.empty((int(qo[-1]), self.Hq, self.D), dtype=np.float32)
+        rc = lib().orc_paged_attn_prefill(C.byref(self.c), layer, _ptr(q), _ptr(out), _ptr(table), table.shape[1],
+                                          _ptr(ctx), _ptr(qo), len(ctx), float(scale), nthreads)
         if rc != OK:
             raise OracleError(rc)
         return out

@@ -472,3 +472,71 @@ int32_t orc_plan_reconfig(int32_t num_gpus, int32_t num_layers, const uint8_t *c
   scalars[3] = b_new;
   return ORC_OK;
 }
+
+/* ------------------------------------------------------- prefill attention
+ * Chunked prefill over the same paged layout (the compute-bound stage of
+ * Sec. 2 "LLM Inference": the prompt's tokens are processed in parallel).
+ * Sequence s has ctx_lens[s] tokens in the cache, the last
+ * q_len = q_offsets[s+1] - q_offsets[s] of them are the new chunk; query row
+ * q_offsets[s] + i sits at position p = ctx - q_len + i and attends to the
+ * cached tokens 0..p (causal).  Decode is the case q_len = 1.
+ *   q   bf16 [total_q][Hq][D],  out fp32 [total_q][Hq][D]                  */
+int32_t orc_paged_attn_prefill(const orc_kv_t *kv, int32_t layer, const uint16_t *q, float *out,
+                               const int32_t *table, int32_t table_stride, const int32_t *ctx_lens,
+                               const int32_t *q_offsets, int32_t num_seqs, double scale,
+                               int32_t nthreads) {
+  if (!kv || layer < 0 || layer >= kv->num_layers || num_seqs < 0) return ORC_E_INVAL;
+  const int Hq = kv->num_q_heads, Hkv = kv->num_kv_heads, D = kv->head_dim, bs = kv->block_tokens;
+  const int G = Hq / Hkv;
+  if (scale <= 0) scale = 1.0 / sqrt((double)D);
+  for (int s = 0; s < num_seqs; ++s) {
+    const int n = ctx_lens[s], ql = q_offsets[s + 1] - q_offsets[s];
+    if (n < 0 || ql < 0 || ql > n || (int64_t)(n + bs - 1) / bs > table_stride) return ORC_E_INVAL;
+    for (int b = 0; b < (n + bs - 1) / bs; ++b) {
+      int32_t id = table[(int64_t)s * table_stride + b];
+      if (id < 0 || id >= kv->num_blocks) return ORC_E_RANGE;
+    }
+  }
+  const int total_q = num_seqs > 0 ? q_offsets[num_seqs] : 0;
+  /* sequence of every query row */
+  int32_t *seq_of = (int32_t *)malloc(sizeof(int32_t) * (size_t)(total_q > 0 ? total_q : 1));
+  for (int s = 0; s < num_seqs; ++s)
+    for (int r = q_offsets[s]; r < q_offsets[s + 1]; ++r) seq_of[r] = s;
+#ifdef _OPENMP
+  if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for num_threads(nthreads) schedule(dynamic, 4)
+#endif
+  for (int rh = 0; rh < total_q * Hq; ++rh) {
+    const int row = rh / Hq, h = rh % Hq, g = h / G;
+    const int s = seq_of[row];
+    const int ql = q_offsets[s + 1] - q_offsets[s];
+    const int p = ctx_lens[s] - ql + (row - q_offsets[s]); /* position of this query */
+    const uint16_t *qh = q + ((int64_t)row * Hq + h) * D;
+    float *o = out + ((int64_t)row * Hq + h) * D;
+    double *x = (double *)malloc(sizeof(double) * (size_t)(p + 1));
+    double *num = (double *)calloc((size_t)D, sizeof(double));
+    double m = -INFINITY;
+    for (int j = 0; j <= p; ++j) {
+      const uint16_t *blk =
+          (const uint16_t *)layer_block(kv, layer, table[(int64_t)s * table_stride + j / bs]);
+      double acc = 0.0;
+      for (int d = 0; d < D; ++d)
+        acc += bf16_to_double(qh[d]) * bf16_to_double(blk[k_elem(kv, g, j % bs, d)]);
+      x[j] = scale * acc;
+      if (x[j] > m) m = x[j];
+    }
+    double den = 0.0;
+    for (int j = 0; j <= p; ++j) {
+      const uint16_t *blk =
+          (const uint16_t *)layer_block(kv, layer, table[(int64_t)s * table_stride + j / bs]);
+      const double w = exp(x[j] - m);
+      den += w;
+      for (int d = 0; d < D; ++d) num[d] += w * bf16_to_double(blk[v_elem(kv, g, j % bs, d)]);
+    }
+    for (int d = 0; d < D; ++d) o[d] = (float)(num[d] / den);
+    free(x);
+    free(num);
+  }
+  free(seq_of);
+  return ORC_OK;
+}
