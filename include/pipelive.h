@@ -140,6 +140,28 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
 size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
                                            int32_t max_ctx, int32_t split_tokens);
 
+/* Chunked-prefill attention of ONE layer over the same KV layout (Sec. 2 "LLM
+ * Inference": the prompt's tokens are processed in parallel; compute-bound).
+ * The new chunk's K/V is already in the cache (pipelive_kv_append or the
+ * caller's own writes).  Sequence s holds ctx_lens[s] cached tokens, of which
+ * the last q_len = q_offsets[s+1] - q_offsets[s] are the chunk; query row
+ * q_offsets[s] + i sits at position ctx_lens[s] - q_len + i and attends to the
+ * cached tokens 0 .. that position (causal).  q_len = 1 is a decode step.
+ *
+ * q          DEVICE bf16 [total_q][Hq][D], rows packed sequence after sequence
+ * out        DEVICE [total_q][Hq][D], fp32 or bf16, 16-B aligned
+ * q_offsets  DEVICE int32 [num_seqs + 1], q_offsets[0] = 0, non-decreasing
+ * total_q    HOST: q_offsets[num_seqs] (sizes the launch)
+ * other arguments as for pipelive_paged_attn_decode; no workspace is needed.
+ * A sequence with more queries than cached tokens sets the status word
+ * (PIPELIVE_E_INVAL) and its rows are not written.  Asynchronous.
+ */
+int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                    int32_t out_dtype, const int32_t *block_table,
+                                    int32_t table_stride, const int32_t *ctx_lens,
+                                    const int32_t *q_offsets, int32_t num_seqs, int32_t total_q,
+                                    int32_t max_ctx, float scale, void *stream);
+
 /* -------------------------------------------------------------------------
  * 2. ResizeKV(B) with compaction (Sec. 4.2 primitive ResizeKV; Alg. 1 phases
  * 1-2 and 5; Sec. 5.1).

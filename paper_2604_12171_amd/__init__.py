@@ -6,5 +6,5 @@ from .binding import *  # noqa: F401,F403
 from .binding import (KVRegion, PipeliveError, load, pipelive_kv_append, pipelive_kv_clear_status,  # noqa: F401
                       pipelive_kv_mark_dirty, pipelive_kv_patch_apply, pipelive_kv_patch_collect,
                       pipelive_kv_read_state, pipelive_kv_resize, pipelive_max_blocks,
-                      pipelive_paged_attn_decode, pipelive_patch_max_blocks, pipelive_plan_reconfig,
+                      pipelive_paged_attn_decode, pipelive_paged_attn_prefill, pipelive_patch_max_blocks, pipelive_plan_reconfig,
                       pipelive_converged)

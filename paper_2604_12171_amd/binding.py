@@ -27,7 +27,7 @@ PATCH_MAGIC = 0x564B4C50
 
 EXPORTS = [
     "pipelive_bitmap_bytes", "pipelive_kv_dirty_units", "pipelive_kv_append", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
-    "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_workspace_bytes",
+    "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_prefill", "pipelive_paged_attn_workspace_bytes",
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
@@ -101,6 +101,9 @@ def load(path: str | None = None):
     L.pipelive_paged_attn_decode.restype = i32
     L.pipelive_paged_attn_decode.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, i32, i32, C.c_float,
                                              i32, vp, sz, vp]
+    L.pipelive_paged_attn_prefill.restype = i32
+    L.pipelive_paged_attn_prefill.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, vp, i32, i32, i32,
+                                              C.c_float, vp]
     L.pipelive_paged_attn_workspace_bytes.restype = sz
     L.pipelive_paged_attn_workspace_bytes.argtypes = [vp, i32, i32, i32]
     L.pipelive_kv_resize.restype = i32
@@ -179,6 +182,17 @@ def pipelive_paged_attn_decode(kv: "KVRegion", layer, q, out, block_table, ctx_l
                                       _p(block_table), stride, _p(ctx_lens), S, int(max_ctx),
                                       float(scale), int(split_tokens), _p(workspace),
                                       workspace.numel() * workspace.element_size(), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_paged_attn_prefill(kv: "KVRegion", layer, q, out, block_table, ctx_lens, q_offsets, total_q,
+                                max_ctx=0, scale=0.0, check=True):
+    """q bf16 [total_q][Hq][D]; out fp32|bf16 same shape; q_offsets int32 [S+1] on the device."""
+    out_dtype = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    rc = load().pipelive_paged_attn_prefill(kv.handle, int(layer), _p(q), _p(out), out_dtype, _p(block_table),
+                                            int(block_table.shape[1]), _p(ctx_lens), _p(q_offsets),
+                                            int(ctx_lens.shape[0]), int(total_q), int(max_ctx), float(scale),
+                                            _stream())
     return _check(rc) if check else rc
 
 

@@ -226,6 +226,46 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
   return PIPELIVE_OK;
 }
 
+int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                    int32_t out_dtype, const int32_t *block_table,
+                                    int32_t table_stride, const int32_t *ctx_lens,
+                                    const int32_t *q_offsets, int32_t num_seqs, int32_t total_q,
+                                    int32_t max_ctx, float scale, void *stream) {
+  if (!kv || !q || !out || !block_table || !ctx_lens || !q_offsets) return PIPELIVE_E_INVAL;
+  if (layer < 0 || layer >= kv->d.num_layers) return PIPELIVE_E_RANGE;
+  if (num_seqs < 0 || total_q < 0 || table_stride <= 0) return PIPELIVE_E_INVAL;
+  if (out_dtype != PIPELIVE_OUT_F32 && out_dtype != PIPELIVE_OUT_BF16) return PIPELIVE_E_INVAL;
+  if (!aligned(q, 16) || !aligned(out, 16)) return PIPELIVE_E_INVAL;
+  if (num_seqs == 0 || total_q == 0) return PIPELIVE_OK;
+  PrefillParams p;
+  p.block_list = kv->d.block_list + (int64_t)(layer / kv->d.stack_k) * kv->d.capacity_blocks;
+  p.layer_off = (uint32_t)((layer % kv->d.stack_k) * kv->blk_bytes);
+  p.q = (const uint16_t *)q;
+  p.out = out;
+  p.out_dtype = out_dtype;
+  p.table = block_table;
+  p.table_stride = table_stride;
+  p.ctx = ctx_lens;
+  p.q_offsets = q_offsets;
+  p.num_seqs = num_seqs;
+  p.max_ctx = effective_max_ctx(kv, table_stride, max_ctx);
+  p.Hq = kv->d.num_q_heads;
+  p.Hkv = kv->d.num_kv_heads;
+  p.G = p.Hq / p.Hkv;
+  const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)kv->d.head_dim);
+  p.scale_log2 = sc * 1.4426950408889634f;
+  // one wave per (sequence, KV head, block of QB query tokens); the ragged split is only
+  // known on the device, so launch the upper bound and let the surplus waves exit
+  const int qb = (kPrefillNQ * 16) / p.G;
+  const int64_t units = (int64_t)p.Hkv * ((total_q + qb - 1) / qb + num_seqs);
+  if (units > (1ll << 30)) return PIPELIVE_E_INVAL;
+  p.num_waves = (int32_t)units;
+  p.num_blocks = kv->d.num_blocks;
+  p.status = &dev_state(kv)->status;
+  HIP_TRY(launch_attn_prefill(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
 /* --------------------------------------------------------------- resize */
 
 size_t pipelive_kv_resize_workspace_bytes(const pipelive_kv_t *kv) {

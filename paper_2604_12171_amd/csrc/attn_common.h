@@ -1,0 +1,95 @@
+// Device helpers shared by the decode and prefill attention kernels (gfx950).
+#pragma once
+#include "internal.h"
+
+namespace pipelive {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, int lane) {
+  uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, lane);
+  uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), lane);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// top 16 bits of two floats packed into one dword: [hi16(a) | hi16(b) << 16]
+__device__ __forceinline__ uint32_t pack_hi16(float a, float b) {
+  return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float o) {
+  uint32_t u = __float_as_uint(o);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
+
+constexpr int kTile = 32;      // tokens per tile
+constexpr int kSubTiles = 32;  // tiles whose block addresses are resolved at once
+
+// KV blocks are reached through 64-bit addresses read from the block list; the
+// explicit global address space keeps the loads global_load (not flat_load).
+typedef const u32x4 __attribute__((address_space(1))) *global_u4;
+typedef const u32x2 __attribute__((address_space(1))) *global_u2;
+
+template <int D>
+struct KRegs {
+  u32x4 k[2][D / 32];
+  int nvalid[2];
+};
+template <int D>
+struct VRegs {
+  u32x2 v[D / 16][2];
+};
+
+// Issue the K loads of one tile.  a0/a1 are the (wave-uniform) block addresses
+// of its two 16-token halves (both always valid memory: a half without tokens
+// re-reads the first half's block and is masked), nv0/nv1 the number of valid
+// tokens in each half.
+template <int D, int BS>
+__device__ __forceinline__ void load_k(KRegs<D> &t, uint64_t a0, uint64_t a1, int nv0, int nv1, int g,
+                                       int r, int qg) {
+  constexpr int NC = D / 32;
+  constexpr int KHEAD = BS * D * 2;
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    const uint64_t addr = T ? a1 : a0;
+    const int nv = T ? nv1 : nv0;
+    t.nvalid[T] = nv > 0 ? nv : 0;
+    const int toff = (BS == 32) ? 16 * T : 0;
+    const uint64_t kb = addr + (uint64_t)g * KHEAD + (uint32_t)((qg * BS + toff + r) * 16);
+#pragma unroll
+    for (int c = 0; c < NC; ++c) t.k[T][c] = *(global_u4)(kb + (uint32_t)(4 * c * BS * 16));
+  }
+}
+
+template <int D, int BS>
+__device__ __forceinline__ void load_v(VRegs<D> &t, uint64_t a0, uint64_t a1, int g, int Hkv, int r,
+                                       int qg) {
+  constexpr int ND = D / 16;
+  constexpr int KHEAD = BS * D * 2;
+#pragma unroll
+  for (int T = 0; T < 2; ++T) {
+    const uint64_t addr = T ? a1 : a0;
+    const int toff = (BS == 32) ? 16 * T : 0;
+    const uint64_t vb = addr + (uint64_t)(Hkv + g) * KHEAD + (uint32_t)((r * BS + toff + 4 * qg) * 2);
+#pragma unroll
+    for (int c = 0; c < ND; ++c) t.v[c][T] = *(global_u2)(vb + (uint32_t)(16 * c * BS * 2));
+  }
+}
+
+}  // namespace pipelive

@@ -68,6 +68,27 @@ __host__ __device__ inline int64_t attn_record_floats(int G, int D) {
 hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st);
 int attn_waves_per_cu(int D, int BS);
 
+// ---- prefill attention
+constexpr int kPrefillNQ = 4;  // 16-column score blocks per wave: 64 (token, head) columns
+struct PrefillParams {
+  const uint64_t *block_list;
+  uint32_t layer_off;
+  const uint16_t *q;
+  void *out;
+  int32_t out_dtype;
+  const int32_t *table;
+  int32_t table_stride;
+  const int32_t *ctx;
+  const int32_t *q_offsets;
+  int32_t num_seqs, max_ctx;
+  int32_t Hq, Hkv, G;
+  float scale_log2;
+  int32_t num_waves;
+  int64_t num_blocks;
+  int32_t *status;
+};
+hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st);
+
 // ---- resize
 struct TableRef {
   int32_t *table;
