@@ -335,6 +335,42 @@ def main():
             "apply_us": round(med(tapl) * 1e3, 1),
             "note": "block-granular patch of the same step carries %d bytes" % (n_dirty * L * cfg.blk_bytes)}
 
+    # ---------------- prefill attention (the compute-bound neighbour of the decode path): the
+    # prefill-heavy pattern, 512-token prompts, and a 512-token chunk on top of 4096 cached tokens
+    if not args.decode_only:
+        MFMA_PEAK_TFLOPS = 2500.0
+        pres = {}
+        for tag, Sp, ctxp, qlp in (("prompt512", 64, 512, 512), ("chunk512_of_4096", 16, 4096, 512)):
+            pcfg = pin.StageConfig(tag, 1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
+                                   Sp, ctxp, ctxp)
+            pb = pin.draw_batch(pcfg, seed, pool_factor=1.25)
+            preg = P.KVRegion(1, pcfg.num_q_heads, pcfg.num_kv_heads, pcfg.head_dim, pcfg.block_tokens,
+                              pb.num_blocks, arenas=3)
+            fill_live_blocks(preg, pcfg, pb, seed, pb.num_blocks, poison_tail=False)
+            qo_d = torch.arange(0, (Sp + 1) * qlp, qlp, dtype=torch.int32, device="cuda")
+            tq = Sp * qlp
+            pq = torch.from_numpy(pin.bf16_normal(pin.stream_key(seed, pin.STREAM_Q), 0, tq * pcfg.num_q_heads *
+                                                  pcfg.head_dim).view(np.int16)).cuda().view(torch.bfloat16)
+            pq = pq.view(tq, pcfg.num_q_heads, pcfg.head_dim)
+            pout = torch.empty((tq, pcfg.num_q_heads, pcfg.head_dim), dtype=torch.float32, device="cuda")
+            pt, pc = torch.from_numpy(pb.table).cuda(), torch.from_numpy(pb.ctx_lens).cuda()
+            for _ in range(2):
+                P.pipelive_paged_attn_prefill(preg, 0, pq, pout, pt, pc, qo_d, tq)
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(10):
+                P.pipelive_paged_attn_prefill(preg, 0, pq, pout, pt, pc, qo_d, tq)
+            e1.record()
+            torch.cuda.synchronize()
+            pms = e0.elapsed_time(e1) / 10
+            pairs = Sp * sum(ctxp - qlp + i + 1 for i in range(qlp))     # (query, visible key) pairs per head
+            flops = pairs * pcfg.num_q_heads * 4 * pcfg.head_dim          # QK^T and PV, 2 flop per MAC
+            pres[tag] = {"seqs": Sp, "ctx": ctxp, "q_len": qlp, "us": round(pms * 1e3, 1),
+                         "TFLOPs": round(flops / pms / 1e9, 1),
+                         "frac_of_mfma_peak": round(flops / pms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+            del preg, pq, pout
+        result["prefill"] = {"bound": "mfma", "peak_TFLOPs": MFMA_PEAK_TFLOPS, "dtype": "bf16", **pres}
+
     # ---------------- CPU oracle on a bounded sample of the same workload
     if not args.no_cpu_baseline:
         import oracle

@@ -18,9 +18,26 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int lane) {
   return ((uint64_t)hi << 32) | lo;
 }
 
-// top 16 bits of two floats packed into one dword: [hi16(a) | hi16(b) << 16]
-__device__ __forceinline__ uint32_t pack_hi16(float a, float b) {
-  return (__float_as_uint(a) >> 16) | (__float_as_uint(b) & 0xFFFF0000u);
+// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, bf16x2));
+}
+
+// Softmax weights as MFMA operands: p = hi + lo with hi = bf16(p) (nearest) and
+// lo = bf16(p - hi); the pair keeps 16 mantissa bits of the fp32 weight.
+__device__ __forceinline__ void split_weights(const float (&pv)[8], u32x4 &ph, u32x4 &pl) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_bf16_rne(pv[2 * i], pv[2 * i + 1]);
+    const float r0 = pv[2 * i] - __uint_as_float(h[i] << 16);
+    const float r1 = pv[2 * i + 1] - __uint_as_float(h[i] & 0xFFFF0000u);
+    l[i] = pack_bf16_rne(r0, r1);
+  }
+  ph = (u32x4){h[0], h[1], h[2], h[3]};
+  pl = (u32x4){l[0], l[1], l[2], l[3]};
 }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float o) {

@@ -93,13 +93,7 @@ __device__ __forceinline__ void qk_softmax(const KRegs<D> &t, const bf16x8 (&qre
     for (int c = 0; c < ND; ++c) acc[c] *= alpha;
   }
   // P^T operand: slots 0..3 = half 0 tokens 4qg+i, slots 4..7 = half 1; two bf16 terms
-  float lo[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) lo[i] = pv[i] - __uint_as_float(__float_as_uint(pv[i]) & 0xFFFF0000u);
-  ph = (u32x4){pack_hi16(pv[0], pv[1]), pack_hi16(pv[2], pv[3]), pack_hi16(pv[4], pv[5]),
-               pack_hi16(pv[6], pv[7])};
-  pl = (u32x4){pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
-               pack_hi16(lo[6], lo[7])};
+  split_weights(pv, ph, pl);
 }
 
 // O^T += V^T P^T.  nv0/nv1: valid tokens of the two halves (as recorded by load_k).

@@ -11,15 +11,17 @@
 // all columns with the K operand fetched once, applies the causal mask by
 // predicate, runs the online softmax per column and accumulates
 // O^T += V^T P^T with P split into two bf16 terms, the V operand again fetched
-// once for all columns.  K/V of the next tile are in flight while the current
-// one is computed (one wave per SIMD, so latency is hidden inside the wave).
+// once for all columns.  The K operand of the next tile is in flight while the
+// current one is computed; V is loaded at the top of its own tile and lands
+// during the score/softmax phase.  NQ = 2 keeps the kernel at 250 VGPRs, so
+// two waves share a SIMD and one's softmax overlaps the other's MFMAs.
 #include "attn_common.h"
 
 namespace pipelive {
 namespace {
 
 template <int D, int BS, int NQ>
-__global__ __launch_bounds__(256, 1) void attn_prefill_kernel(PrefillParams p) {
+__global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   constexpr int NC = D / 32, ND = D / 16;
   const int lane = threadIdx.x & 63;
   const int gw = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
@@ -50,7 +52,8 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_kernel(PrefillParams p) {
     }
   }
   if (s < 0) return;  // beyond the last unit
-  const int g = (int)(rem / nqb), qb = (int)(rem % nqb);
+  // later query blocks attend to more tokens: hand them out first so the launch ends evenly
+  const int g = (int)(rem / nqb), qb = nqb - 1 - (int)(rem % nqb);
   const int q0 = p.q_offsets[s], qlen = p.q_offsets[s + 1] - q0;
   int n = p.ctx[s];
   if (n > p.max_ctx) n = p.max_ctx;
@@ -81,8 +84,7 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_kernel(PrefillParams p) {
       qreg[nq][c] = as_bf16x8(v);
     }
   }
-  int p_min = p_max;  // smallest causal limit over all lanes' columns (wave-uniform): pos0
-  p_min = pos0;
+  const int p_min = pos0;  // smallest causal limit over the unit's columns (wave-uniform)
 
   f32x4 acc[ND][NQ];
   float m[NQ], l[NQ];
@@ -141,13 +143,7 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int c = 0; c < ND; ++c) acc[c][nq] *= alpha;
       }
-      float lo[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) lo[i] = pv[i] - __uint_as_float(__float_as_uint(pv[i]) & 0xFFFF0000u);
-      ph[nq] = (u32x4){pack_hi16(pv[0], pv[1]), pack_hi16(pv[2], pv[3]), pack_hi16(pv[4], pv[5]),
-                       pack_hi16(pv[6], pv[7])};
-      pl[nq] = (u32x4){pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]), pack_hi16(lo[4], lo[5]),
-                       pack_hi16(lo[6], lo[7])};
+      split_weights(pv, ph[nq], pl[nq]);
     }
     // V of tokens past the readable range must be zero (0 * NaN is NaN)
 #pragma unroll
@@ -201,23 +197,24 @@ __global__ __launch_bounds__(256, 1) void attn_prefill_kernel(PrefillParams p) {
       nv0 = min(n_kv - t0, 16);
       nv1 = min(n_kv - t0 - 16, 16);
     };
+    // Two waves per SIMD overlap each other's loads and arithmetic; K of the next tile is
+    // requested before the current tile is computed, V is fetched tile by tile.
     KRegs<D> kc, kn;
-    VRegs<D> vc, vn;
+    VRegs<D> vc;
     uint64_t a0, a1;
     int nv0, nv1;
     addr_of(0, a0, a1, nv0, nv1);
     load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
-    load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
 #pragma unroll 1
-    for (int i = 0; i + 1 < nt; ++i) {
-      addr_of(i + 1, a0, a1, nv0, nv1);
-      load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
-      load_v<D, BS>(vn, a0, a1, g, Hkv, r, qg);
+    for (int i = 0; i < nt; ++i) {
+      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
+      if (i + 1 < nt) {
+        addr_of(i + 1, a0, a1, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
+      }
       compute(kc, vc, sub + i);
       kc = kn;
-      vc = vn;
     }
-    compute(kc, vc, sub + nt - 1);
   }
 
   // ---- normalise and store: lane (qg, r) holds O[column r of block nq][16c + 4qg + i]

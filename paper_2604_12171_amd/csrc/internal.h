@@ -69,7 +69,7 @@ hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st
 int attn_waves_per_cu(int D, int BS);
 
 // ---- prefill attention
-constexpr int kPrefillNQ = 4;  // 16-column score blocks per wave: 64 (token, head) columns
+constexpr int kPrefillNQ = 2;  // 16-column score blocks per wave: 32 (token, head) columns
 struct PrefillParams {
   const uint64_t *block_list;
   uint32_t layer_off;
