@@ -57,6 +57,8 @@ extern "C" {
 #define PIPELIVE_OUT_F32 0
 #define PIPELIVE_OUT_BF16 1
 #define PIPELIVE_MAX_PATCH_LAYERS 128
+#define PIPELIVE_BACKING_ARENA 0
+#define PIPELIVE_BACKING_PER_BLOCK 1
 #define PIPELIVE_MAX_TABLES 8
 #define PIPELIVE_PATCH_MAGIC 0x564B4C50u /* bytes 'P','L','K','V' */
 #define PIPELIVE_PATCH_VERSION 1u
@@ -69,17 +71,22 @@ typedef struct {
   int32_t num_q_heads;     /* Hq */
   int32_t num_kv_heads;    /* Hkv, divides Hq; query head h reads KV head h / (Hq/Hkv) */
   int32_t head_dim;        /* D: 64 or 128 */
-  int32_t block_tokens;    /* bs: 16 or 32 tokens per block */
+  int32_t block_tokens;    /* bs: 16, 32, 64 or 128 tokens per block */
   int32_t stack_k;         /* layers per physical block (Sec. 5.2); 1 = one pool per layer */
   int32_t dtype;           /* PIPELIVE_DTYPE_BF16 */
   int32_t in_block_layout; /* PIPELIVE_LAYOUT_D8 */
   int32_t dirty_granularity; /* PIPELIVE_DIRTY_BLOCK: one dirty bit per block id;
                                 PIPELIVE_DIRTY_SLOT: one per token slot (unit id = block id * bs + slot),
                                 the paper's own granularity (Sec. 6.1) */
-  int32_t reserved0;       /* 0 */
+  int32_t block_backing;   /* PIPELIVE_BACKING_ARENA: blocks lie inside larger allocations, a shrink
+                              vacates ids >= B_new by copying (block_list is only read);
+                              PIPELIVE_BACKING_PER_BLOCK: every physical block is an allocation of its
+                              own (Sec. 5.1), a shrink permutes block_list in place (pointer updates
+                              only) and the caller releases the blocks left at ids >= B_new */
   int64_t num_blocks;      /* B: valid ids are 0 .. B-1 */
   int64_t capacity_blocks; /* entries per group in block_list, B <= capacity < 2^31 */
-  const uint64_t *block_list; /* DEVICE [ceil(L/stack_k)][capacity]: block addresses, 256-B aligned */
+  const uint64_t *block_list; /* DEVICE [ceil(L/stack_k)][capacity]: block addresses, 256-B aligned;
+                                 written by pipelive_kv_resize when block_backing is PER_BLOCK */
   uint8_t *live_bitmap;    /* DEVICE, pipelive_bitmap_bytes(capacity): bit i = byte i>>3, bit i&7;
                               maintained by the caller's block manager, updated by resize */
   uint8_t *dirty_bitmap;   /* DEVICE, pipelive_bitmap_bytes(U) with U = pipelive_kv_dirty_units(capacity, bs,
@@ -175,6 +182,11 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
  * order (every layer's bytes are copied), the live bitmap and every used
  * table entry follow, and B becomes new_num_blocks.  Blocks that stay keep
  * their ids; bytes below new_num_blocks that no move targets are untouched.
+ * With PIPELIVE_BACKING_PER_BLOCK no byte is copied: for every move the two
+ * block_list entries (of every layer group) are exchanged, so the moved id
+ * names the same physical block as before under its new id - the same
+ * logical result - and the physical blocks that were free end up at ids >=
+ * new_num_blocks, ready to be released.
  * Grow (new_num_blocks > B, <= capacity; the caller has filled the new
  * block_list entries): B becomes new_num_blocks, the new ids are not live, no
  * data moves.
@@ -202,6 +214,63 @@ int32_t pipelive_kv_resize(pipelive_kv_t *kv, int64_t new_num_blocks, int32_t *c
                            int32_t *remap_out, pipelive_resize_result_t *result, void *workspace,
                            size_t workspace_bytes, void *stream);
 size_t pipelive_kv_resize_workspace_bytes(const pipelive_kv_t *kv);
+
+/* -------------------------------------------------------------------------
+ * Independently allocated blocks (Sec. 5.1: the KV cache is a list of GPU
+ * blocks that are allocated and freed on demand; Sec. 5.2: such allocations
+ * come in units of the virtual-memory allocation granularity).
+ *
+ * A pool reserves one virtual address range of max_blocks * block_bytes and
+ * backs single blocks of it with physical memory through HIP's virtual memory
+ * management calls.  pipelive_vmm_pool_alloc / _free are the only calls of
+ * this library that allocate or release device memory; they are host-side
+ * driver calls (tens to hundreds of microseconds per block) and belong
+ * outside the serving loop.  A pool is bound to the device that was current
+ * at creation and is not thread-safe.
+ *
+ * Together with PIPELIVE_BACKING_PER_BLOCK a shrink is:
+ *   pipelive_kv_resize(kv, B_new, ...)         permutes block_list, remaps tables
+ *   read block_list[g][B_new .. B_old) back    the blocks no id refers to any more
+ *   pipelive_vmm_pool_free(pool, n, addrs)     returns their memory to the device
+ * and a grow is pipelive_vmm_pool_alloc, write the addresses to
+ * block_list[g][B_old .. B_new), pipelive_kv_resize(kv, B_new, ...).
+ */
+typedef struct pipelive_vmm_pool pipelive_vmm_pool_t;
+
+/* Physical memory one block of `block_bytes` consumes: block_bytes rounded up
+ * to the 2 MiB unit in which MI355X backs such allocations (measured: the
+ * runtime reports a 4 KiB granularity, free memory drops by 2 MiB per handle). */
+size_t pipelive_vmm_backing_bytes(size_t block_bytes);
+
+/* block_bytes: a multiple of the granularity the runtime reports (E_INVAL
+ * otherwise); max_blocks: size of the address range, in blocks.  No physical
+ * memory is taken.  E_HIP if the device has no virtual memory management. */
+int32_t pipelive_vmm_pool_create(size_t block_bytes, int64_t max_blocks, pipelive_vmm_pool_t **out);
+/* unmaps and releases every block still allocated, frees the address range */
+void pipelive_vmm_pool_destroy(pipelive_vmm_pool_t *pool);
+/* Back n more blocks (lowest free positions of the range first) and return
+ * their device addresses in addrs (HOST, n entries).  E_NOSPACE if fewer than n
+ * positions are free, E_HIP if the device is out of memory; in both cases
+ * nothing stays allocated from this call. */
+int32_t pipelive_vmm_pool_alloc(pipelive_vmm_pool_t *pool, int64_t n, uint64_t *addrs);
+/* Release the blocks at addrs (HOST, n entries, each returned by _alloc and not
+ * yet freed; E_INVAL otherwise, checked before anything is released).  No
+ * kernel may be using them: the caller synchronises first. */
+int32_t pipelive_vmm_pool_free(pipelive_vmm_pool_t *pool, int64_t n, const uint64_t *addrs);
+/* blocks currently backed by physical memory; -1 for a null pool */
+int64_t pipelive_vmm_pool_allocated(const pipelive_vmm_pool_t *pool);
+/* first address of the pool's range (position i lies at base + i * block_bytes); 0 for a null pool */
+uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *pool);
+
+/* Effective KV utilisation (Sec. 7.5, effects of layer stacking): tokens held
+ * divided by token slots of the blocks the sequences occupy,
+ *   sum_s n_s / sum_s ceil(n_s / block_tokens) * block_tokens ;  1.0 when no
+ * sequence holds a token.  ctx_lens HOST int32 [n].  Host arithmetic only. */
+double pipelive_kv_utilization(const int32_t *ctx_lens, int64_t n, int32_t block_tokens);
+/* Tokens per layer in one physical block of `phys_block_bytes` shared by
+ * stack_k layers (Sec. 5.2: C / k): floor(phys_block_bytes / (stack_k * token_bytes_per_layer)). */
+int64_t pipelive_stacked_block_tokens(size_t phys_block_bytes, int32_t stack_k,
+                                      size_t token_bytes_per_layer);
 
 /* MaxBlocks(i, L) = floor((M_i * u - L * W) / (L * P))  (Alg. 1); host arithmetic only. */
 int64_t pipelive_max_blocks(double mem_bytes, double util, int64_t layers,

@@ -40,6 +40,7 @@ class _KV(C.Structure):
         ("num_blocks", C.c_int64), ("capacity_blocks", C.c_int64),
         ("block_list", C.c_void_p), ("live_bitmap", C.c_void_p), ("dirty_bitmap", C.c_void_p),
         ("n_acc", C.c_uint64), ("t_applied", C.c_uint64),
+        ("per_block", C.c_int32), ("pad_", C.c_int32),
     ]
 
 
@@ -72,6 +73,10 @@ def lib():
                                          C.c_void_p]
         L.orc_max_blocks.restype = C.c_int64
         L.orc_max_blocks.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double]
+        L.orc_kv_utilization.restype = C.c_double
+        L.orc_kv_utilization.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
+        L.orc_stacked_block_tokens.restype = C.c_int64
+        L.orc_stacked_block_tokens.argtypes = [C.c_uint64, C.c_int32, C.c_uint64]
         L.orc_paged_attn_prefill.restype = C.c_int32
         L.orc_paged_attn_prefill.argtypes = [C.POINTER(_KV), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                              C.c_int32, C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_int32]
@@ -99,7 +104,7 @@ class HostKV:
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens,
                  num_blocks, capacity_blocks=None, layout=0, stack_k=1, arenas=3,
-                 fill_bits=0xFFFF, dirty_gran=0):
+                 fill_bits=0xFFFF, dirty_gran=0, per_block=False):
         self.L, self.Hq, self.Hkv, self.D, self.bs = num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens
         self.layout, self.stack_k = layout, stack_k
         self.capacity = int(capacity_blocks if capacity_blocks is not None else num_blocks)
@@ -125,7 +130,9 @@ class HostKV:
         self.c = _KV(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, stack_k,
                      layout, dirty_gran, int(num_blocks), self.capacity,
                      self.block_list.ctypes.data, self.live.ctypes.data, self.dirty.ctypes.data,
-                     0, 0)
+                     0, 0, int(bool(per_block)), 0)
+        self.per_block = bool(per_block)
+        self._arena_base = np.array([a.ctypes.data for a in self.arenas], dtype=np.uint64)
 
     # ---- state access
     @property
@@ -142,11 +149,15 @@ class HostKV:
 
     def block(self, layer: int, block_id: int) -> np.ndarray:
         """uint16 view [blk_elems] of (layer, block)."""
-        b = int(block_id)
-        arr = self.arenas[(layer // self.stack_k) * self._n_ar + b % self._n_ar]
-        k = b // self._n_ar
-        o = (layer % self.stack_k) * self.blk_elems
-        return arr[k, o:o + self.blk_elems]
+        g = layer // self.stack_k
+        addr = int(self.block_list[g, int(block_id)])  # follows the block list: a shrink may permute it
+        phys = self.blk_bytes * self.stack_k
+        for a in range(g * self._n_ar, (g + 1) * self._n_ar):
+            off = addr - int(self._arena_base[a])
+            if 0 <= off < self.arenas[a].nbytes:
+                o = (layer % self.stack_k) * self.blk_elems
+                return self.arenas[a][off // phys, o:o + self.blk_elems]
+        raise IndexError(f"block {block_id} of layer {layer} has no memory")
 
     def set_live(self, ids) -> None:
         self.live[:] = 0
@@ -251,6 +262,15 @@ def parse_patch_header(patch: np.ndarray) -> dict:
 def max_blocks(mem_bytes, util, layers, weight_bytes_per_layer, block_bytes_per_layer) -> int:
     return int(lib().orc_max_blocks(mem_bytes, util, layers, weight_bytes_per_layer,
                                     block_bytes_per_layer))
+
+
+def kv_utilization(ctx_lens, block_tokens) -> float:
+    c = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    return float(lib().orc_kv_utilization(c.ctypes.data, len(c), int(block_tokens)))
+
+
+def stacked_block_tokens(phys_bytes, k, token_bytes_per_layer) -> int:
+    return int(lib().orc_stacked_block_tokens(int(phys_bytes), int(k), int(token_bytes_per_layer)))
 
 
 def plan_reconfig(cur_sets, tgt_sets, num_layers, mem_bytes, util, weight_bytes_per_layer,

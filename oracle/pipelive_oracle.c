@@ -52,6 +52,9 @@ typedef struct {
   uint8_t *dirty_bitmap;
   uint64_t n_acc;        /* tokens marked since the last complete drain */
   uint64_t t_applied;    /* tokens acknowledged by applied patches */
+  int32_t per_block;     /* 1: every physical block is an allocation of its own, so a shrink
+                            exchanges block-list entries instead of copying (Sec. 5.1) */
+  int32_t pad_;
 } orc_kv_t;
 
 typedef struct {
@@ -193,6 +196,11 @@ int32_t orc_paged_attn_decode(const orc_kv_t *kv, int32_t layer, const uint16_t 
  *   block T[k] moves to F[k] in every layer; remap[T[k]] = F[k]; other live
  *   ids map to themselves; non-live ids map to -1; every used table entry e
  *   becomes remap[e]; live bits follow the blocks; B <- B_new.
+ * With independently allocated blocks (per_block) the move of T[k] to F[k]
+ * is the exchange of the two block-list entries in every layer group: id
+ * F[k] then names the physical block T[k] named, no byte is copied, and the
+ * free physical blocks collect at the ids >= B_new (Sec. 5.1: compaction
+ * moves the unallocated blocks to the end of the list by pointer updates).
  * Grow to B_new > B (<= capacity): B <- B_new, new ids not live, no data
  * moves (Sec. 5.1: expansion appends blocks to the block list).
  * result[0..3] = n_live, n_moved, old B, new B. */
@@ -228,9 +236,15 @@ int32_t orc_kv_resize(orc_kv_t *kv, int64_t new_num_blocks, int32_t **tables,
       if (!get_bit(kv->live_bitmap, t)) continue;
       while (get_bit(kv->live_bitmap, f)) ++f; /* f < new_num_blocks since n_live <= B_new */
       for (int64_t grp = 0; grp < num_groups(kv); ++grp) {
-        uint8_t *src = (uint8_t *)(uintptr_t)kv->block_list[grp * kv->capacity_blocks + t];
-        uint8_t *dst = (uint8_t *)(uintptr_t)kv->block_list[grp * kv->capacity_blocks + f];
-        memcpy(dst, src, bytes);
+        uint64_t *et = &kv->block_list[grp * kv->capacity_blocks + t];
+        uint64_t *ef = &kv->block_list[grp * kv->capacity_blocks + f];
+        if (kv->per_block) {
+          uint64_t tmp = *et;
+          *et = *ef;
+          *ef = tmp;
+        } else {
+          memcpy((uint8_t *)(uintptr_t)*ef, (const uint8_t *)(uintptr_t)*et, bytes);
+        }
       }
       remap[t] = (int32_t)f;
       set_bit(kv->live_bitmap, f);
@@ -419,6 +433,27 @@ int64_t orc_max_blocks(double mem_bytes, double util, int64_t layers, double wei
   double v = (mem_bytes * util - (double)layers * weight_bytes_per_layer) /
              ((double)layers * block_bytes_per_layer);
   return v < 0 ? 0 : (int64_t)floor(v);
+}
+
+/* Effective KV utilisation (Sec. 7.5): tokens held / token slots of the blocks
+ * the sequences occupy, a sequence of n tokens occupying ceil(n / bs) blocks. */
+double orc_kv_utilization(const int32_t *ctx_lens, int64_t n, int32_t block_tokens) {
+  double tokens = 0.0, slots = 0.0;
+  for (int64_t s = 0; s < n; ++s) {
+    if (ctx_lens[s] <= 0) continue;
+    int64_t blocks = 0;
+    while (blocks * block_tokens < ctx_lens[s]) ++blocks;
+    tokens += (double)ctx_lens[s];
+    slots += (double)(blocks * block_tokens);
+  }
+  return slots > 0.0 ? tokens / slots : 1.0;
+}
+
+/* Tokens per layer in a physical block of `phys_bytes` shared by k layers (Sec. 5.2: C / k). */
+int64_t orc_stacked_block_tokens(uint64_t phys_bytes, int32_t k, uint64_t token_bytes_per_layer) {
+  int64_t t = 0;
+  while ((uint64_t)(t + 1) * (uint64_t)k * token_bytes_per_layer <= phys_bytes) ++t;
+  return t;
 }
 
 /* ------------------------------------------------------------------ planner

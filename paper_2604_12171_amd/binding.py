@@ -20,6 +20,7 @@ from . import build as _build
 OK, E_INVAL, E_INFEASIBLE, E_NOSPACE, E_BUSY, E_RANGE, E_HIP = 0, -1, -2, -3, -4, -5, -6
 LAYOUT_D8 = 0
 DIRTY_BLOCK, DIRTY_SLOT = 0, 1
+BACKING_ARENA, BACKING_PER_BLOCK = 0, 1
 OUT_F32, OUT_BF16 = 0, 1
 MAX_PATCH_LAYERS = 128
 MAX_TABLES = 8
@@ -31,6 +32,8 @@ EXPORTS = [
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
+    "pipelive_vmm_backing_bytes", "pipelive_vmm_pool_create", "pipelive_vmm_pool_destroy", "pipelive_vmm_pool_alloc",
+    "pipelive_vmm_pool_free", "pipelive_vmm_pool_allocated", "pipelive_vmm_pool_base", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
     "pipelive_kv_clear_status", "pipelive_plan_reconfig", "pipelive_converged", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
 ]
 
@@ -40,7 +43,7 @@ class KVDesc(C.Structure):
         ("num_layers", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
         ("head_dim", C.c_int32), ("block_tokens", C.c_int32), ("stack_k", C.c_int32),
         ("dtype", C.c_int32), ("in_block_layout", C.c_int32),
-        ("dirty_granularity", C.c_int32), ("reserved0", C.c_int32),
+        ("dirty_granularity", C.c_int32), ("block_backing", C.c_int32),
         ("num_blocks", C.c_int64), ("capacity_blocks", C.c_int64),
         ("block_list", C.c_void_p), ("live_bitmap", C.c_void_p), ("dirty_bitmap", C.c_void_p),
         ("dev_state", C.c_void_p),
@@ -130,6 +133,24 @@ def load(path: str | None = None):
                                          i64, C.POINTER(ReconfigPlan), vp, i32, vp, i32]
     L.pipelive_converged.restype = i32
     L.pipelive_converged.argtypes = [i64, vp, i32, i64]
+    L.pipelive_vmm_backing_bytes.restype = sz
+    L.pipelive_vmm_backing_bytes.argtypes = [sz]
+    L.pipelive_vmm_pool_create.restype = i32
+    L.pipelive_vmm_pool_create.argtypes = [sz, i64, C.POINTER(vp)]
+    L.pipelive_vmm_pool_destroy.restype = None
+    L.pipelive_vmm_pool_destroy.argtypes = [vp]
+    L.pipelive_vmm_pool_alloc.restype = i32
+    L.pipelive_vmm_pool_alloc.argtypes = [vp, i64, vp]
+    L.pipelive_vmm_pool_free.restype = i32
+    L.pipelive_vmm_pool_free.argtypes = [vp, i64, vp]
+    L.pipelive_vmm_pool_allocated.restype = i64
+    L.pipelive_vmm_pool_allocated.argtypes = [vp]
+    L.pipelive_vmm_pool_base.restype = C.c_uint64
+    L.pipelive_vmm_pool_base.argtypes = [vp]
+    L.pipelive_kv_utilization.restype = C.c_double
+    L.pipelive_kv_utilization.argtypes = [vp, i64, i32]
+    L.pipelive_stacked_block_tokens.restype = i64
+    L.pipelive_stacked_block_tokens.argtypes = [sz, i32, sz]
     L.pipelive_strerror.restype = C.c_char_p
     L.pipelive_strerror.argtypes = [i32]
     L.pipelive_last_hip_error.restype = C.c_char_p
@@ -291,19 +312,78 @@ def pipelive_converged(t_sched, t_applied, tau) -> bool:
     return bool(load().pipelive_converged(int(t_sched), arr, len(t_applied), int(tau)))
 
 
+def pipelive_kv_utilization(ctx_lens, block_tokens) -> float:
+    arr = _i32_array(ctx_lens)
+    return float(load().pipelive_kv_utilization(arr, len(ctx_lens), int(block_tokens)))
+
+
+def pipelive_stacked_block_tokens(phys_block_bytes, stack_k, token_bytes_per_layer) -> int:
+    return int(load().pipelive_stacked_block_tokens(int(phys_block_bytes), int(stack_k),
+                                                    int(token_bytes_per_layer)))
+
+
+def pipelive_vmm_backing_bytes(block_bytes) -> int:
+    return int(load().pipelive_vmm_backing_bytes(int(block_bytes)))
+
+
+class VmmPool:
+    """Handle of one pipelive_vmm_pool: blocks of device memory allocated and released one by one."""
+
+    def __init__(self, block_bytes: int, max_blocks: int):
+        h = C.c_void_p()
+        _check(load().pipelive_vmm_pool_create(int(block_bytes), int(max_blocks), C.byref(h)))
+        self.handle, self.block_bytes, self.max_blocks = h, int(block_bytes), int(max_blocks)
+
+    def alloc(self, n: int) -> list[int]:
+        out = (C.c_uint64 * max(int(n), 1))()
+        _check(load().pipelive_vmm_pool_alloc(self.handle, int(n), out))
+        return [int(out[i]) for i in range(int(n))]
+
+    def free(self, addrs) -> None:
+        arr = (C.c_uint64 * max(len(addrs), 1))(*[int(a) for a in addrs])
+        _check(load().pipelive_vmm_pool_free(self.handle, len(addrs), arr))
+
+    @property
+    def allocated(self) -> int:
+        return int(load().pipelive_vmm_pool_allocated(self.handle))
+
+    def close(self) -> None:
+        if self.handle:
+            load().pipelive_vmm_pool_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class _DeviceSpan:
+    """Presents a range of device addresses to torch (no copy, no ownership)."""
+
+    def __init__(self, addr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (int(nbytes) // 2,), "typestr": "<i2",
+                                         "data": (int(addr), False), "version": 2}
+
+
 # ---- device memory plumbing ------------------------------------------------------
 
 class KVRegion:
     """Torch allocations + library handle of one KV region on the current device.
 
-    Physical blocks are spread over ``arenas`` separate allocations per layer
-    group (block ``b`` in arena ``b % arenas``) so that no address is
-    ``base + id * stride``.  ``backed_blocks`` limits how many ids get real
-    memory (the rest of the block list is null and must not be used)."""
+    ``backing="arena"``: physical blocks are spread over ``arenas`` separate torch
+    allocations per layer group (block ``b`` in arena ``b % arenas``) so that no
+    address is ``base + id * stride``; all ``capacity`` ids are backed.
+    ``backing="vmm"``: every physical block is an allocation of its own from a
+    :class:`VmmPool` (shuffled positions); only ids below ``num_blocks`` are
+    backed, :meth:`grow_backing` and :meth:`release_tail` follow a resize."""
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
                  capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda",
-                 dirty_granularity=DIRTY_BLOCK, share_pool_of: "KVRegion | None" = None):
+                 dirty_granularity=DIRTY_BLOCK, share_pool_of: "KVRegion | None" = None,
+                 backing="arena"):
+        import numpy as np
         L = load()
         if not torch.cuda.is_available():
             raise RuntimeError("pipelive needs a GPU: no CPU fallback exists")
@@ -314,15 +394,30 @@ class KVRegion:
         self.blk_bytes = 2 * self.blk_elems
         self.groups = (num_layers + stack_k - 1) // stack_k
         self.device = torch.device(device)
+        self.backing = backing
+        self.pool = None
+        self._bl_host = None
+        self._fill = None if fill_bits is None else (fill_bits - 65536 if fill_bits >= 32768 else fill_bits)
         phys = self.blk_elems * stack_k
+        self.phys_bytes = 2 * phys
         if share_pool_of is not None:
             # a second handle over the same physical blocks (own dirty bitmap and state),
             # e.g. to track the same pool at another dirty granularity
             o = share_pool_of
             assert (o.L_, o.Hkv, o.D, o.bs, o.stack_k, o.capacity) == (num_layers, num_kv_heads, head_dim,
                                                                       block_tokens, stack_k, self.capacity)
+            assert o.backing == "arena" and backing == "arena"
             self._n_ar, self.arenas, self.block_list = o._n_ar, o.arenas, o.block_list
+        elif backing == "vmm":
+            slots = self.groups * self.capacity
+            self.pool = VmmPool(self.phys_bytes, slots)
+            self._pool_base = int(L.pipelive_vmm_pool_base(self.pool.handle))
+            self._pool_view = None  # made at the first allocation: torch wants a mapped first byte
+            self._bl_host = np.zeros((self.groups, self.capacity), dtype=np.int64)
+            self.block_list = torch.zeros((self.groups, self.capacity), dtype=torch.int64, device=self.device)
+            self._back(0, int(num_blocks))
         else:
+            assert backing == "arena"
             self._n_ar = n_ar = max(1, min(arenas, self.capacity))
             self.arenas = []
             bl = torch.zeros((self.groups, self.capacity), dtype=torch.int64)
@@ -330,8 +425,8 @@ class KVRegion:
                 for a in range(n_ar):
                     cnt = len(range(a, self.capacity, n_ar))
                     t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
-                    if fill_bits is not None:
-                        t.fill_(fill_bits - 65536 if fill_bits >= 32768 else fill_bits)
+                    if self._fill is not None:
+                        t.fill_(self._fill)
                     self.arenas.append(t)
                     bl[g, a::n_ar] = t.data_ptr() + torch.arange(cnt, dtype=torch.int64) * (phys * 2)
             self.block_list = bl.to(self.device)
@@ -344,7 +439,8 @@ class KVRegion:
         self.dirty = torch.zeros(L.pipelive_bitmap_bytes(units), dtype=torch.uint8, device=self.device)
         self.state = torch.zeros(L.pipelive_kv_state_bytes(units), dtype=torch.uint8, device=self.device)
         d = KVDesc(num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, stack_k, 0,
-                   LAYOUT_D8, dirty_granularity, 0, int(num_blocks), self.capacity, self.block_list.data_ptr(),
+                   LAYOUT_D8, dirty_granularity, BACKING_PER_BLOCK if backing == "vmm" else BACKING_ARENA,
+                   int(num_blocks), self.capacity, self.block_list.data_ptr(),
                    self.live.data_ptr(), self.dirty.data_ptr(), self.state.data_ptr())
         h = C.c_void_p()
         torch.cuda.synchronize()
@@ -357,6 +453,10 @@ class KVRegion:
             if getattr(self, "handle", None):
                 load().pipelive_kv_destroy(self.handle)
                 self.handle = None
+            if getattr(self, "pool", None) is not None:
+                torch.cuda.synchronize()
+                self._pool_view = None
+                self.pool.close()
         except Exception:
             pass
 
@@ -364,34 +464,87 @@ class KVRegion:
     def num_blocks(self) -> int:
         return int(load().pipelive_kv_num_blocks(self.handle))
 
+    # ---- per-block backing: allocate for a grow, release after a shrink
+    def _back(self, lo: int, hi: int) -> None:
+        """allocate physical blocks for ids [lo, hi) of every group and enter them in the block list"""
+        import numpy as np
+        if hi <= lo:
+            return
+        n = (hi - lo) * self.groups
+        addrs = np.array(self.pool.alloc(n), dtype=np.int64)
+        if self._pool_view is None:
+            # one view over the whole address range; only rows with physical memory are ever indexed
+            slots = self.groups * self.capacity
+            self._pool_view = torch.as_tensor(_DeviceSpan(self._pool_base, slots * self.phys_bytes),
+                                              device=self.device).view(slots, self.phys_bytes // 2)
+        addrs = addrs[np.random.default_rng(lo * 7919 + hi).permutation(n)]  # no address = base + id * stride
+        if self._fill is not None:
+            rows = torch.from_numpy((addrs - self._pool_base) // self.phys_bytes).to(self.device)
+            self._pool_view[rows] = self._fill
+        self._bl_host[:, lo:hi] = addrs.reshape(self.groups, hi - lo)
+        self.block_list[:, lo:hi] = torch.from_numpy(self._bl_host[:, lo:hi]).to(self.device)
+
+    def grow_backing(self, new_num_blocks: int) -> None:
+        """before a grow: back ids [num_blocks, new_num_blocks)"""
+        assert self.backing == "vmm" and new_num_blocks <= self.capacity
+        self._back(self.num_blocks, int(new_num_blocks))
+
+    def release_tail(self, old_num_blocks: int) -> int:
+        """after a shrink: return the physical blocks left at ids [num_blocks, old_num_blocks) to the
+        device; returns how many were released"""
+        assert self.backing == "vmm"
+        lo, hi = self.num_blocks, int(old_num_blocks)
+        if hi <= lo:
+            return 0
+        torch.cuda.synchronize()
+        self._bl_host = self.block_list.cpu().numpy().copy()  # the resize permuted it on the device
+        tail = self._bl_host[:, lo:hi].reshape(-1)
+        self.pool.free([int(a) for a in tail])
+        self._bl_host[:, lo:hi] = 0
+        self.block_list[:, lo:hi] = 0
+        return int(tail.size)
+
+    def _where(self, layer: int, ids):
+        """[(tensor, selector over ids, rows)]: where the physical blocks of `ids` lie"""
+        g = layer // self.stack_k
+        if self.backing == "vmm":
+            if self._bl_host is None:
+                self._bl_host = self.block_list.cpu().numpy().copy()
+            rows = (self._bl_host[g, ids.numpy()] - self._pool_base) // self.phys_bytes
+            assert (rows >= 0).all(), "block id without physical memory"
+            return [(self._pool_view, torch.ones(len(ids), dtype=torch.bool), torch.from_numpy(rows))]
+        out = []
+        for a in range(self._n_ar):
+            sel = (ids % self._n_ar) == a
+            if sel.any():
+                out.append((self.arenas[g * self._n_ar + a], sel, ids[sel] // self._n_ar))
+        return out
+
+    def sync_block_list(self) -> None:
+        """re-read the block list after the library permuted it (per-block backing, shrink)"""
+        if self.backing == "vmm":
+            torch.cuda.synchronize()
+            self._bl_host = self.block_list.cpu().numpy().copy()
+
     def block(self, layer: int, block_id: int) -> torch.Tensor:
         """int16 view [blk_elems] of (layer, block) in device memory."""
-        b = int(block_id)
-        t = self.arenas[(layer // self.stack_k) * self._n_ar + b % self._n_ar]
+        t, _, rows = self._where(layer, torch.tensor([int(block_id)], dtype=torch.int64))[0]
         o = (layer % self.stack_k) * self.blk_elems
-        return t[b // self._n_ar, o:o + self.blk_elems]
+        return t[int(rows[0]), o:o + self.blk_elems]
 
     def write_blocks(self, layer: int, block_ids, data: torch.Tensor) -> None:
         """data: int16 [n][blk_elems] on the device -> blocks ``block_ids`` of ``layer``."""
         ids = torch.tensor([int(b) for b in block_ids], dtype=torch.int64)
         o = (layer % self.stack_k) * self.blk_elems
-        for a in range(self._n_ar):
-            sel = (ids % self._n_ar) == a
-            if sel.any():
-                t = self.arenas[(layer // self.stack_k) * self._n_ar + a]
-                rows = (ids[sel] // self._n_ar).to(self.device)
-                t[rows, o:o + self.blk_elems] = data[sel.to(data.device)]
+        for t, sel, rows in self._where(layer, ids):
+            t[rows.to(self.device), o:o + self.blk_elems] = data[sel.to(data.device)]
 
     def read_blocks(self, layer: int, block_ids) -> torch.Tensor:
         ids = torch.tensor([int(b) for b in block_ids], dtype=torch.int64)
         out = torch.empty((len(ids), self.blk_elems), dtype=torch.int16, device=self.device)
         o = (layer % self.stack_k) * self.blk_elems
-        for a in range(self._n_ar):
-            sel = (ids % self._n_ar) == a
-            if sel.any():
-                t = self.arenas[(layer // self.stack_k) * self._n_ar + a]
-                rows = (ids[sel] // self._n_ar).to(self.device)
-                out[sel.to(self.device)] = t[rows, o:o + self.blk_elems]
+        for t, sel, rows in self._where(layer, ids):
+            out[sel.to(self.device)] = t[rows.to(self.device), o:o + self.blk_elems]
         return out
 
     def set_live(self, ids) -> None:

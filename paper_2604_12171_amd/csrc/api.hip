@@ -15,16 +15,6 @@ namespace {
 
 thread_local char g_hip_err[256] = "";
 
-int32_t hip_fail(hipError_t e) {
-  snprintf(g_hip_err, sizeof g_hip_err, "%s", hipGetErrorString(e));
-  return PIPELIVE_E_HIP;
-}
-#define HIP_TRY(expr)                          \
-  do {                                         \
-    hipError_t e_ = (expr);                    \
-    if (e_ != hipSuccess) return hip_fail(e_); \
-  } while (0)
-
 inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -33,6 +23,11 @@ int g_cu_count = 0;
 }  // namespace
 
 namespace pipelive {
+void set_hip_error(const char *text) { snprintf(g_hip_err, sizeof g_hip_err, "%s", text); }
+int32_t hip_fail(hipError_t e) {
+  set_hip_error(hipGetErrorString(e));
+  return PIPELIVE_E_HIP;
+}
 int device_cu_count() {
   if (g_cu_count == 0) {
     int dev = 0, n = 0;
@@ -80,7 +75,10 @@ int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
   if (d->num_q_heads % d->num_kv_heads) return PIPELIVE_E_INVAL;
   if (d->num_q_heads / d->num_kv_heads > 16) return PIPELIVE_E_INVAL;
   if (d->head_dim != 64 && d->head_dim != 128) return PIPELIVE_E_INVAL;
-  if (d->block_tokens != 16 && d->block_tokens != 32) return PIPELIVE_E_INVAL;
+  if (d->block_tokens != 16 && d->block_tokens != 32 && d->block_tokens != 64 && d->block_tokens != 128)
+    return PIPELIVE_E_INVAL;
+  if (d->block_backing != PIPELIVE_BACKING_ARENA && d->block_backing != PIPELIVE_BACKING_PER_BLOCK)
+    return PIPELIVE_E_INVAL;
   if (d->stack_k < 1 || d->dtype != PIPELIVE_DTYPE_BF16) return PIPELIVE_E_INVAL;
   if (d->in_block_layout != PIPELIVE_LAYOUT_D8) return PIPELIVE_E_INVAL;
   if (d->dirty_granularity != PIPELIVE_DIRTY_BLOCK && d->dirty_granularity != PIPELIVE_DIRTY_SLOT)

@@ -231,10 +231,12 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
     for (int sub = 0; sub < cnt; sub += kSubTiles) {
       const int jb = j0 + sub;                        // first tile of this batch
       const int nt = min(cnt - sub, kSubTiles);       // tiles in this batch
-      // resolve the batch's blocks: one block per lane
-      constexpr int BPT = kTile / BS;                 // blocks per tile: 2 or 1
-      const int first_blk = jb * BPT;
-      const int nblk = min(nt * BPT, (n + BS - 1) / BS - first_blk);
+      // resolve the batch's blocks: one block per lane (a block holds half a tile,
+      // one tile, or TPB tiles)
+      constexpr int TPB = BS >= kTile ? BS / kTile : 1;
+      const int first_blk = BS < kTile ? jb * 2 : jb / TPB;
+      const int last_blk = BS < kTile ? (jb + nt) * 2 - 1 : (jb + nt - 1) / TPB;
+      const int nblk = min(last_blk + 1, (n + BS - 1) / BS) - first_blk;
       uint64_t my_addr = 0;
       bool bad = false;
       if (lane < nblk) {
@@ -246,14 +248,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
         if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
         continue;
       }
-      // tile i of the batch: block addresses and valid-token counts of its halves
-      auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
+      // tile i of the batch: block addresses of its two halves, the tile's token
+      // offset inside its block, and the valid-token counts of the halves
+      auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &o, int &nv0, int &nv1) {
         const int tok0 = (jb + i) * kTile;
-        if (BS == 16) {
+        if (BS < kTile) {
           a0 = readlane64(my_addr, 2 * i);
           a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
+          o = 0;
         } else {
-          a0 = a1 = readlane64(my_addr, i);
+          a0 = a1 = readlane64(my_addr, (jb + i) / TPB - first_blk);
+          o = ((jb + i) % TPB) * kTile;
         }
         nv0 = min(n - tok0, 16);
         nv1 = min(n - tok0 - 16, 16);
@@ -263,17 +268,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       KRegs<D> kc, kn;
       VRegs<D> vc, vn;
       uint64_t a0, a1;
-      int nv0, nv1;
-      addr_of(0, a0, a1, nv0, nv1);
-      load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
-      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
+      int o, nv0, nv1;
+      addr_of(0, a0, a1, o, nv0, nv1);
+      load_k<D, BS>(kc, a0, a1, o, nv0, nv1, g, r, qg);
+      load_v<D, BS>(vc, a0, a1, o, g, Hkv, r, qg);
 #pragma unroll 1
       for (int i = 0; i + 1 < nt; ++i) {
-        addr_of(i + 1, a0, a1, nv0, nv1);
-        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
+        addr_of(i + 1, a0, a1, o, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, o, nv0, nv1, g, r, qg);
         u32x4 ph, pl;
         qk_softmax<D>(kc, qreg, acc, m, l, p.scale_log2, qg, ph, pl);
-        load_v<D, BS>(vn, a0, a1, g, Hkv, r, qg);
+        load_v<D, BS>(vn, a0, a1, o, g, Hkv, r, qg);
         pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
         kc = kn;
         vc = vn;
@@ -452,24 +457,28 @@ int occupancy_t() {
 
 }  // namespace
 
+// one instantiation per (head_dim, block_tokens) the interface admits
+#define PIPELIVE_ATTN_SHAPES(X) \
+  X(128, 16) X(128, 32) X(128, 64) X(128, 128) X(64, 16) X(64, 32) X(64, 64) X(64, 128)
+
 hipError_t launch_attn_decode(const AttnParams &p, int D, int BS, hipStream_t st) {
-  if (D == 128 && BS == 16) return launch_t<128, 16>(p, st);
-  if (D == 128 && BS == 32) return launch_t<128, 32>(p, st);
-  if (D == 64 && BS == 16) return launch_t<64, 16>(p, st);
-  if (D == 64 && BS == 32) return launch_t<64, 32>(p, st);
+#define X(d, b) \
+  if (D == d && BS == b) return launch_t<d, b>(p, st);
+  PIPELIVE_ATTN_SHAPES(X)
+#undef X
   return hipErrorInvalidValue;
 }
 
 int attn_waves_per_cu(int D, int BS) {
-  static int cache[4] = {0, 0, 0, 0};
-  const int idx = (D == 128 ? 0 : 2) + (BS == 16 ? 0 : 1);
-  if (cache[idx] == 0) {
-    if (D == 128 && BS == 16) cache[idx] = occupancy_t<128, 16>();
-    else if (D == 128 && BS == 32) cache[idx] = occupancy_t<128, 32>();
-    else if (D == 64 && BS == 16) cache[idx] = occupancy_t<64, 16>();
-    else cache[idx] = occupancy_t<64, 32>();
+#define X(d, b)                                   \
+  if (D == d && BS == b) {                        \
+    static int cached = 0;                        \
+    if (cached == 0) cached = occupancy_t<d, b>(); \
+    return cached;                                \
   }
-  return cache[idx];
+  PIPELIVE_ATTN_SHAPES(X)
+#undef X
+  return 4;
 }
 
 }  // namespace pipelive

@@ -172,9 +172,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 
   for (int sub = 0; sub < nt_all; sub += kSubTiles) {
     const int nt = min(nt_all - sub, kSubTiles);
-    constexpr int BPT = kTile / BS;
-    const int first_blk = sub * BPT;
-    const int nblk = min(nt * BPT, (n_kv + BS - 1) / BS - first_blk);
+    constexpr int TPB = BS >= kTile ? BS / kTile : 1;  // tiles per block (a 16-token block is half a tile)
+    const int first_blk = BS < kTile ? sub * 2 : sub / TPB;
+    const int last_blk = BS < kTile ? (sub + nt) * 2 - 1 : (sub + nt - 1) / TPB;
+    const int nblk = min(last_blk + 1, (n_kv + BS - 1) / BS) - first_blk;
     uint64_t my_addr = 0;
     bool bad = false;
     if (lane < nblk) {
@@ -186,13 +187,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
       continue;
     }
-    auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
+    auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &o, int &nv0, int &nv1) {
       const int t0 = (sub + i) * kTile;
-      if (BS == 16) {
+      if (BS < kTile) {
         a0 = readlane64(my_addr, 2 * i);
         a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
+        o = 0;
       } else {
-        a0 = a1 = readlane64(my_addr, i);
+        a0 = a1 = readlane64(my_addr, (sub + i) / TPB - first_blk);
+        o = ((sub + i) % TPB) * kTile;  // token offset of the tile inside its block
       }
       nv0 = min(n_kv - t0, 16);
       nv1 = min(n_kv - t0 - 16, 16);
@@ -202,15 +205,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     KRegs<D> kc, kn;
     VRegs<D> vc;
     uint64_t a0, a1;
-    int nv0, nv1;
-    addr_of(0, a0, a1, nv0, nv1);
-    load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
+    int o, nv0, nv1;
+    addr_of(0, a0, a1, o, nv0, nv1);
+    load_k<D, BS>(kc, a0, a1, o, nv0, nv1, g, r, qg);
 #pragma unroll 1
     for (int i = 0; i < nt; ++i) {
-      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
+      load_v<D, BS>(vc, a0, a1, o, g, Hkv, r, qg);
       if (i + 1 < nt) {
-        addr_of(i + 1, a0, a1, nv0, nv1);
-        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
+        addr_of(i + 1, a0, a1, o, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, o, nv0, nv1, g, r, qg);
       }
       compute(kc, vc, sub + i);
       kc = kn;
@@ -256,10 +259,10 @@ hipError_t launch_t(const PrefillParams &p, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st) {
-  if (D == 128 && BS == 16) return launch_t<128, 16>(p, st);
-  if (D == 128 && BS == 32) return launch_t<128, 32>(p, st);
-  if (D == 64 && BS == 16) return launch_t<64, 16>(p, st);
-  if (D == 64 && BS == 32) return launch_t<64, 32>(p, st);
+#define X(d, b) \
+  if (D == d && BS == b) return launch_t<d, b>(p, st);
+  X(128, 16) X(128, 32) X(128, 64) X(128, 128) X(64, 16) X(64, 32) X(64, 64) X(64, 128)
+#undef X
   return hipErrorInvalidValue;
 }
 

@@ -128,4 +128,14 @@ hipError_t launch_clear_status(const pipelive_kv *kv, hipStream_t st);
 int device_cu_count();
 int copy_wgs_per_cu();  // persistent copy workgroups launched per CU
 
+// the calling thread's last HIP error text (what pipelive_last_hip_error returns)
+void set_hip_error(const char *text);
+int32_t hip_fail(hipError_t e);  // records the text, returns PIPELIVE_E_HIP
+
 }  // namespace pipelive
+
+#define HIP_TRY(expr)                                    \
+  do {                                                   \
+    hipError_t e_ = (expr);                              \
+    if (e_ != hipSuccess) return pipelive::hip_fail(e_); \
+  } while (0)

@@ -129,6 +129,20 @@ __global__ __launch_bounds__(kCopyThreads) void move_kernel(MoveArgs a) {
   }
 }
 
+// Per-block backing: a move exchanges the two block_list entries of every
+// group instead of copying bytes (the sets of sources and targets are
+// disjoint, so the exchanges are independent).
+__global__ void swap_kernel(uint64_t *block_list, int64_t capacity, int32_t groups, int64_t n_moved,
+                            const int32_t *move_src, const int32_t *move_dst) {
+  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
+  if (i >= n_moved * groups) return;
+  uint64_t *bl = block_list + (i % groups) * capacity;
+  const int64_t k = i / groups;
+  const uint64_t a = bl[move_src[k]], b = bl[move_dst[k]];
+  bl[move_src[k]] = b;
+  bl[move_dst[k]] = a;
+}
+
 // remap[b] for b in [0,B): identity if live and kept, -1 if not live; moved
 // ids are written from the move list (disjoint from the first set).
 __global__ void remap_kernel(const u64 *live, int64_t B, int64_t B_new, int64_t n_moved,
@@ -196,7 +210,13 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
                                 const int32_t *move_src, const int32_t *move_dst, int32_t *remap,
                                 const TableRef *tables, int n_tables, hipStream_t st) {
   hipError_t e;
-  if (n_moved > 0) {
+  if (n_moved > 0 && kv->d.block_backing == PIPELIVE_BACKING_PER_BLOCK) {
+    const int64_t n = n_moved * kv->groups;
+    hipLaunchKernelGGL(swap_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       const_cast<uint64_t *>(kv->d.block_list), kv->d.capacity_blocks,
+                       (int32_t)kv->groups, n_moved, move_src, move_dst);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+  } else if (n_moved > 0) {
     MoveArgs a;
     a.block_list = kv->d.block_list;
     a.capacity = kv->d.capacity_blocks;

@@ -102,4 +102,21 @@ int32_t pipelive_converged(int64_t t_sched, const int64_t *t_applied, int32_t n,
   return 1;
 }
 
+double pipelive_kv_utilization(const int32_t *ctx_lens, int64_t n, int32_t block_tokens) {
+  if (!ctx_lens || n <= 0 || block_tokens <= 0) return 1.0;
+  int64_t tokens = 0, slots = 0;
+  for (int64_t s = 0; s < n; ++s) {
+    const int64_t c = ctx_lens[s] > 0 ? ctx_lens[s] : 0;
+    tokens += c;
+    slots += (c + block_tokens - 1) / block_tokens * block_tokens;
+  }
+  return slots == 0 ? 1.0 : (double)tokens / (double)slots;
+}
+
+int64_t pipelive_stacked_block_tokens(size_t phys_block_bytes, int32_t stack_k,
+                                      size_t token_bytes_per_layer) {
+  if (stack_k <= 0 || token_bytes_per_layer == 0) return 0;
+  return (int64_t)(phys_block_bytes / ((size_t)stack_k * token_bytes_per_layer));
+}
+
 }  // extern "C"

@@ -26,16 +26,17 @@ def live_block_bits(cfg, batch, seed, capacity, epoch, layer):
     return out
 
 
-def make_pair(cfg, batch, seed, capacity=None, num_layers=None, stack_k=1, arenas=3):
-    """(HostKV, KVRegion) holding the same blocks; everything else is NaN."""
+def make_pair(cfg, batch, seed, capacity=None, num_layers=None, stack_k=1, arenas=3, backing="arena"):
+    """(HostKV, KVRegion) holding the same blocks; everything else is NaN.  backing="vmm": every
+    device block is an allocation of its own and the oracle resizes by block-list exchange."""
     L = num_layers or cfg.num_layers
     cap = capacity or batch.num_blocks
     host = oracle.HostKV(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
                          batch.num_blocks, capacity_blocks=cap, layout=cfg.layout, stack_k=stack_k,
-                         arenas=arenas, fill_bits=pin.BF16_NAN)
+                         arenas=arenas, fill_bits=pin.BF16_NAN, per_block=backing == "vmm")
     dev = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
                      batch.num_blocks, capacity_blocks=cap, stack_k=stack_k, arenas=arenas + 1,
-                     fill_bits=pin.BF16_NAN)
+                     fill_bits=pin.BF16_NAN, backing=backing)
     return host, dev
 
 

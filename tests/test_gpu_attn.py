@@ -44,7 +44,8 @@ RAGGED = [0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 0, 257, 700, 1029, 2100
 
 
 @pytest.mark.parametrize("shape", [(4, 2, 64, 16), (32, 8, 128, 16), (64, 8, 128, 16), (32, 8, 128, 32),
-                                   (8, 8, 128, 16), (16, 1, 64, 32)])
+                                   (8, 8, 128, 16), (16, 1, 64, 32), (32, 8, 128, 64), (32, 8, 128, 128),
+                                   (4, 2, 64, 128), (8, 1, 64, 64)])
 @pytest.mark.parametrize("split", [0, 32, 64, 256, 1024, 4096])
 def test_attention_matches_oracle(shape, split):
     Hq, Hkv, D, bs = shape

@@ -38,7 +38,8 @@ def _make(layout, L, Hq, Hkv, D, bs, ctx, seed, B=None, stack_k=1, stride_pad=0)
 
 
 @pytest.mark.parametrize("layout", [0, 1])
-@pytest.mark.parametrize("shape", [(4, 2, 64, 16), (8, 2, 128, 32), (3, 3, 64, 16), (8, 1, 128, 16)])
+@pytest.mark.parametrize("shape", [(4, 2, 64, 16), (8, 2, 128, 32), (3, 3, 64, 16), (8, 1, 128, 16),
+                                   (4, 2, 64, 64), (4, 1, 128, 128)])
 def test_paged_equals_dense(layout, shape):
     Hq, Hkv, D, bs = shape
     ctx = [1, 15, 16, 17, 63, 100, 0, 33]

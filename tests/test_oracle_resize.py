@@ -73,6 +73,50 @@ def test_brute_force_all_subsets_of_8_blocks():
                         assert np.array_equal(kv.block(l, b), before[l][b])
 
 
+def test_per_block_mode_permutes_the_block_list_and_copies_nothing():
+    """Sec. 5.1: with independently allocated blocks compaction is pointer updates only.  On every
+    subset of an 8-block pool the logical outcome (remap, table, live set, content by id) equals the
+    copying mode's, the block list is a permutation of itself, unmoved ids keep their address, the
+    addresses left at ids >= B_new belong to blocks nobody uses, and no arena byte changes."""
+    B = 8
+    for mask in range(1 << B):
+        live = {b for b in range(B) if mask >> b & 1}
+        for B_new in range(len(live), B + 1):
+            kv = oracle.HostKV(4, 2, 1, 8, 2, B, arenas=3, stack_k=2, per_block=True)
+            ref = oracle.HostKV(4, 2, 1, 8, 2, B, arenas=3, stack_k=2)
+            _fill_blocks(kv, seed=mask)
+            _fill_blocks(ref, seed=mask)
+            before = _snapshot(kv)
+            arenas0 = [a.copy() for a in kv.arenas]
+            bl0 = kv.block_list.copy()
+            for r in (kv, ref):
+                r.set_live(sorted(live))
+            tabs = [np.array([sorted(live) + [pin.TABLE_FILL]], dtype=np.int32) for _ in range(2)]
+            used = np.array([len(live)], dtype=np.int32)
+            rc, remap, res = kv.resize(B_new, [tabs[0]], [used])
+            rc2, remap2, res2 = ref.resize(B_new, [tabs[1]], [used])
+            assert rc == rc2 == oracle.OK
+            assert np.array_equal(remap, remap2) and list(res) == list(res2)
+            assert np.array_equal(tabs[0], tabs[1]) and np.array_equal(kv.live, ref.live)
+            for a0, a1 in zip(arenas0, kv.arenas):
+                assert np.array_equal(a0, a1)                      # nothing was copied
+            exp, _ = _definition(live, B, B_new)
+            for g in range(kv.groups):
+                assert sorted(kv.block_list[g]) == sorted(bl0[g])  # a permutation
+                for b in live:
+                    assert kv.block_list[g, exp[b]] == bl0[g, b]   # the id took its physical block along
+                used_addrs = {int(bl0[g, b]) for b in live}
+                for b in range(B_new, B):
+                    assert int(kv.block_list[g, b]) not in used_addrs
+                for b in range(B_new):
+                    if b not in {exp[x] for x in live if exp[x] != x}:
+                        assert kv.block_list[g, b] == bl0[g, b]
+            for l in range(kv.L):
+                for b in live:
+                    assert np.array_equal(kv.block(l, exp[b]), before[l][b])
+                    assert np.array_equal(kv.block(l, exp[b]), ref.block(l, exp[b]))
+
+
 def _tiny_region(seed=pin.MASTER_SEED, B=128, stack_k=1):
     cfg = pin.CONFIGS["tiny"]
     bt = pin.draw_batch(cfg, seed, num_blocks=B)
