@@ -405,6 +405,76 @@ def main():
                       f"{cfg.num_q_heads} heads, {Lc * batch.total_tokens} token-layers), {tc:.2f} s wall on "
                       f"{ncores} threads",
             "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_rel_l2": math.sqrt(num / den)}
+    # ---------------- independently allocated, layer-stacked blocks: the same batch over a pool of
+    # 2 MiB physical blocks (k = 4 layers x 128 tokens), decode, pointer-only shrink, real release
+    if not args.decode_only:
+        sreg = stgt = None      # second handles over the same pools
+        del region, target, patch, ws, qs
+        torch.cuda.empty_cache()
+        k_stack, bs_v = 4, 128
+        vcfg = pin.StageConfig(cfg.name + "-stacked", L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, bs_v,
+                               S, cfg.ctx_lo, cfg.ctx_hi)
+        v_live = int(((ctx.astype(np.int64) + bs_v - 1) // bs_v).sum())
+        Bv = int(v_live * 1.5)
+        t0 = time.perf_counter()
+        vreg = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, bs_v, Bv, stack_k=k_stack,
+                          backing="vmm")
+        t_alloc = time.perf_counter() - t0
+        vb = pin.draw_batch(vcfg, seed, num_blocks=Bv)
+        fill_live_blocks(vreg, vcfg, vb, seed, Bv, poison_tail=True)
+        vt, vc, vu = (torch.from_numpy(x).cuda() for x in (vb.table, vb.ctx_lens, vb.used))
+        vq = torch.from_numpy(pin.q_bits(vcfg, seed, 0).view(np.int16)).cuda().view(torch.bfloat16)
+        vout = torch.empty((S, cfg.num_q_heads, cfg.head_dim), dtype=torch.float32, device="cuda")
+        vmax = int(vb.ctx_lens.max())
+        vws = vreg.attn_workspace(S, vmax, 0)
+
+        def vdecode():
+            for l in range(L):
+                P.pipelive_paged_attn_decode(vreg, l, vq, vout, vt, vc, max_ctx=vmax, workspace=vws)
+        for _ in range(3):
+            vdecode()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(10):
+            vdecode()
+        e1.record()
+        torch.cuda.synchronize()
+        v_ms = e0.elapsed_time(e1) / 10
+        v_bytes = L * (vb.total_tokens * cfg.token_bytes + q_bytes + out_bytes + 4 * int(vb.used.sum()))
+        ref_out = vout.clone()
+        Bv_new = int(Bv * 0.8)
+        v_moved = int((vb.live_ids >= Bv_new).sum())
+        vrws = vreg.resize_workspace()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rc, res = P.pipelive_kv_resize(vreg, Bv_new, [vt], [vu], workspace=vrws)
+        torch.cuda.synchronize()
+        t_shrink = time.perf_counter() - t0
+        if rc != P.OK or res.n_moved != v_moved:
+            raise RuntimeError(f"stacked shrink failed: rc={rc} moved={res.n_moved} expected={v_moved}")
+        free_a = torch.cuda.mem_get_info()[0]
+        t0 = time.perf_counter()
+        n_rel = vreg.release_tail(Bv)
+        t_rel = time.perf_counter() - t0
+        free_b = torch.cuda.mem_get_info()[0]
+        vdecode()
+        torch.cuda.synchronize()
+        if not torch.equal(vout, ref_out):
+            raise RuntimeError("decode changed after the pointer-only shrink")
+        tok = cfg.token_bytes
+        util = {str(k): round(P.pipelive_kv_utilization(ctx, P.pipelive_stacked_block_tokens(2 << 20, k, tok)), 4)
+                for k in (1, 2, 4, 8, 16)}
+        result["stacked_vmm"] = {
+            "stack_k": k_stack, "block_tokens": bs_v, "phys_block_bytes": vreg.phys_bytes,
+            "pool_blocks": Bv, "groups": vreg.groups, "alloc_ms": round(t_alloc * 1e3, 1),
+            "decode_GBps": round(v_bytes / v_ms / 1e6, 1), "decode_frac_of_peak": round(v_bytes / v_ms / 1e6 / 8000.0, 4),
+            "shrink_to": Bv_new, "ids_remapped": v_moved, "bytes_copied": 0,
+            "shrink_us": round(t_shrink * 1e6, 1), "released_blocks": n_rel,
+            "release_ms": round(t_rel * 1e3, 1), "returned_GiB": round((free_b - free_a) / 2**30, 2),
+            "effective_kv_utilization_vs_k": util,
+            "note": "shrink_us is host wall time of pipelive_kv_resize incl. its one sync; release is driver time"}
+        del vreg
+
     print(json.dumps(result), flush=True)
 
 

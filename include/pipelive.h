@@ -25,12 +25,16 @@
  * of layer group `g = layer / stack_k` is at block_list[g * capacity + id];
  * layer `l` occupies bytes [(l % stack_k) * blk, +blk) of it, where
  *     blk = 2 (K,V) * num_kv_heads * block_tokens * head_dim * 2 bytes (bf16).
- * In-block layout 0 (PIPELIVE_LAYOUT_D8), element offsets in bf16 units:
- *     K[g][t][d] at ((g * (D/8) + d/8) * bs + t) * 8 + d % 8
- *     V[g][t][d] at Hkv*bs*D + (g * D + d) * bs + t
- * i.e. K is stored as [Hkv][D/8][bs][8] (16-byte token vectors, token-major
- * inside a d-slice) and V as [Hkv][D][bs] (token-contiguous), so that both
- * MFMA operands of the decode kernel are fetched with fully coalesced loads.
+ * In-block layout 0 (PIPELIVE_LAYOUT_D8): a layer's block is a sequence of
+ * sub-blocks of sb = min(block_tokens, 32) tokens; token t lies in sub-block
+ * u = t / sb at position tt = t % sb.  Element offsets in bf16 units:
+ *     K[g][t][d] at u * (2*Hkv*sb*D) + ((g * (D/8) + d/8) * sb + tt) * 8 + d % 8
+ *     V[g][t][d] at u * (2*Hkv*sb*D) + Hkv*sb*D + (g * D + d) * sb + tt
+ * i.e. inside a sub-block K is stored as [Hkv][D/8][sb][8] (16-byte token
+ * vectors, token-major inside a d-slice) and V as [Hkv][D][sb]
+ * (token-contiguous), so that both MFMA operands of a 32-token tile are
+ * fetched with fully coalesced loads from two contiguous runs per KV head,
+ * whatever the block size.
  */
 #ifndef PIPELIVE_H
 #define PIPELIVE_H

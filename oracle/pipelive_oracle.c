@@ -107,18 +107,27 @@ static uint8_t *layer_block(const orc_kv_t *kv, int layer, int64_t id) {
 
 /* element index (in bf16 units from the start of the layer's block) of
  * K[g][t][d] and V[g][t][d], for the two in-block layouts:
- *   layout 0: K[Hkv][D/8][bs][8] then V[Hkv][D][bs]
- *   layout 1: K[Hkv][bs][D]      then V[Hkv][bs][D]                    */
+ *   layout 0: the block is a sequence of sub-blocks of sb = min(bs, 32)
+ *             tokens; sub-block u holds tokens u*sb .. u*sb+sb-1 as
+ *             K[Hkv][D/8][sb][8] then V[Hkv][D][sb]
+ *   layout 1: K[Hkv][bs][D] then V[Hkv][bs][D]                          */
 static int64_t k_elem(const orc_kv_t *kv, int g, int t, int d) {
   int64_t bs = kv->block_tokens, D = kv->head_dim;
-  if (kv->layout == 0) return (((int64_t)g * (D / 8) + d / 8) * bs + t) * 8 + d % 8;
+  if (kv->layout == 0) {
+    int64_t sb = bs < 32 ? bs : 32, u = t / sb, tt = t % sb;
+    int64_t sub = u * (2 * (int64_t)kv->num_kv_heads * sb * D);
+    return sub + (((int64_t)g * (D / 8) + d / 8) * sb + tt) * 8 + d % 8;
+  }
   return ((int64_t)g * bs + t) * D + d;
 }
 static int64_t v_elem(const orc_kv_t *kv, int g, int t, int d) {
   int64_t bs = kv->block_tokens, D = kv->head_dim;
-  int64_t v0 = (int64_t)kv->num_kv_heads * bs * D;
-  if (kv->layout == 0) return v0 + ((int64_t)g * D + d) * bs + t;
-  return v0 + ((int64_t)g * bs + t) * D + d;
+  if (kv->layout == 0) {
+    int64_t sb = bs < 32 ? bs : 32, u = t / sb, tt = t % sb;
+    int64_t sub = u * (2 * (int64_t)kv->num_kv_heads * sb * D);
+    return sub + (int64_t)kv->num_kv_heads * sb * D + ((int64_t)g * D + d) * sb + tt;
+  }
+  return (int64_t)kv->num_kv_heads * bs * D + ((int64_t)g * bs + t) * D + d;
 }
 
 int32_t orc_struct_bytes(void) { return (int32_t)sizeof(orc_kv_t); }

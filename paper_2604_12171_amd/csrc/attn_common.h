@@ -73,40 +73,52 @@ struct VRegs {
   u32x2 v[D / 16][2];
 };
 
-// Issue the K loads of one tile.  a0/a1 are the (wave-uniform) block addresses
-// of its two 16-token halves (both always valid memory: a half without tokens
-// re-reads the first half's block and is masked), o the token offset of the
-// tile inside its block (0 unless a block holds several tiles), nv0/nv1 the
-// number of valid tokens in each half.
+// In-block layout: a block of BS tokens is a sequence of sub-blocks of
+// SB = min(BS, 32) tokens; a sub-block holds K[Hkv][D/8][SB][8] and then
+// V[Hkv][D][SB] (bf16), so the operands of one 32-token tile are two runs of
+// contiguous memory per KV head whatever the block size.
+template <int BS>
+struct SubBlock {
+  static constexpr int SB = BS < kTile ? BS : kTile;
+  __device__ static uint32_t bytes(int Hkv, int D) { return (uint32_t)(2 * Hkv * SB * D * 2); }
+};
+
+// Issue the K loads of one tile.  a0/a1 are the (wave-uniform) addresses of
+// the sub-blocks holding its two 16-token halves (the same sub-block twice
+// when SB = 32; both always valid memory: a half without tokens re-reads the
+// first half's sub-block and is masked), nv0/nv1 the number of valid tokens in
+// each half.
 template <int D, int BS>
-__device__ __forceinline__ void load_k(KRegs<D> &t, uint64_t a0, uint64_t a1, int o, int nv0, int nv1,
-                                       int g, int r, int qg) {
+__device__ __forceinline__ void load_k(KRegs<D> &t, uint64_t a0, uint64_t a1, int nv0, int nv1, int g,
+                                       int r, int qg) {
   constexpr int NC = D / 32;
-  constexpr int KHEAD = BS * D * 2;
+  constexpr int SB = SubBlock<BS>::SB;
+  constexpr int KHEAD = SB * D * 2;
 #pragma unroll
   for (int T = 0; T < 2; ++T) {
     const uint64_t addr = T ? a1 : a0;
     const int nv = T ? nv1 : nv0;
     t.nvalid[T] = nv > 0 ? nv : 0;
-    const int toff = (BS >= kTile) ? o + 16 * T : 0;
-    const uint64_t kb = addr + (uint64_t)g * KHEAD + (uint32_t)((qg * BS + toff + r) * 16);
+    const int toff = (SB == kTile) ? 16 * T : 0;
+    const uint64_t kb = addr + (uint64_t)g * KHEAD + (uint32_t)((qg * SB + toff + r) * 16);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) t.k[T][c] = *(global_u4)(kb + (uint32_t)(4 * c * BS * 16));
+    for (int c = 0; c < NC; ++c) t.k[T][c] = *(global_u4)(kb + (uint32_t)(4 * c * SB * 16));
   }
 }
 
 template <int D, int BS>
-__device__ __forceinline__ void load_v(VRegs<D> &t, uint64_t a0, uint64_t a1, int o, int g, int Hkv,
-                                       int r, int qg) {
+__device__ __forceinline__ void load_v(VRegs<D> &t, uint64_t a0, uint64_t a1, int g, int Hkv, int r,
+                                       int qg) {
   constexpr int ND = D / 16;
-  constexpr int KHEAD = BS * D * 2;
+  constexpr int SB = SubBlock<BS>::SB;
+  constexpr int KHEAD = SB * D * 2;
 #pragma unroll
   for (int T = 0; T < 2; ++T) {
     const uint64_t addr = T ? a1 : a0;
-    const int toff = (BS >= kTile) ? o + 16 * T : 0;
-    const uint64_t vb = addr + (uint64_t)(Hkv + g) * KHEAD + (uint32_t)((r * BS + toff + 4 * qg) * 2);
+    const int toff = (SB == kTile) ? 16 * T : 0;
+    const uint64_t vb = addr + (uint64_t)(Hkv + g) * KHEAD + (uint32_t)((r * SB + toff + 4 * qg) * 2);
 #pragma unroll
-    for (int c = 0; c < ND; ++c) t.v[c][T] = *(global_u2)(vb + (uint32_t)(16 * c * BS * 2));
+    for (int c = 0; c < ND; ++c) t.v[c][T] = *(global_u2)(vb + (uint32_t)(16 * c * SB * 2));
   }
 }
 

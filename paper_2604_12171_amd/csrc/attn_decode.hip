@@ -248,17 +248,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
         if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
         continue;
       }
-      // tile i of the batch: block addresses of its two halves, the tile's token
-      // offset inside its block, and the valid-token counts of the halves
-      auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &o, int &nv0, int &nv1) {
+      // tile i of the batch: addresses of the sub-blocks of its two halves and
+      // the valid-token counts of the halves
+      const uint32_t sub_bytes = SubBlock<BS>::bytes(Hkv, D);
+      auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
         const int tok0 = (jb + i) * kTile;
         if (BS < kTile) {
           a0 = readlane64(my_addr, 2 * i);
           a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
-          o = 0;
         } else {
-          a0 = a1 = readlane64(my_addr, (jb + i) / TPB - first_blk);
-          o = ((jb + i) % TPB) * kTile;
+          a0 = a1 = readlane64(my_addr, (jb + i) / TPB - first_blk) +
+                    (uint64_t)(((jb + i) % TPB) * sub_bytes);
         }
         nv0 = min(n - tok0, 16);
         nv1 = min(n - tok0 - 16, 16);
@@ -268,17 +268,17 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       KRegs<D> kc, kn;
       VRegs<D> vc, vn;
       uint64_t a0, a1;
-      int o, nv0, nv1;
-      addr_of(0, a0, a1, o, nv0, nv1);
-      load_k<D, BS>(kc, a0, a1, o, nv0, nv1, g, r, qg);
-      load_v<D, BS>(vc, a0, a1, o, g, Hkv, r, qg);
+      int nv0, nv1;
+      addr_of(0, a0, a1, nv0, nv1);
+      load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
+      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
 #pragma unroll 1
       for (int i = 0; i + 1 < nt; ++i) {
-        addr_of(i + 1, a0, a1, o, nv0, nv1);
-        load_k<D, BS>(kn, a0, a1, o, nv0, nv1, g, r, qg);
+        addr_of(i + 1, a0, a1, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
         u32x4 ph, pl;
         qk_softmax<D>(kc, qreg, acc, m, l, p.scale_log2, qg, ph, pl);
-        load_v<D, BS>(vn, a0, a1, o, g, Hkv, r, qg);
+        load_v<D, BS>(vn, a0, a1, g, Hkv, r, qg);
         pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
         kc = kn;
         vc = vn;

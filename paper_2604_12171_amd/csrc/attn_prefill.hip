@@ -187,15 +187,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
       continue;
     }
-    auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &o, int &nv0, int &nv1) {
+    const uint32_t sub_bytes = SubBlock<BS>::bytes(Hkv, D);
+    auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
       const int t0 = (sub + i) * kTile;
       if (BS < kTile) {
         a0 = readlane64(my_addr, 2 * i);
         a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
-        o = 0;
-      } else {
-        a0 = a1 = readlane64(my_addr, (sub + i) / TPB - first_blk);
-        o = ((sub + i) % TPB) * kTile;  // token offset of the tile inside its block
+      } else {  // the tile's 32-token sub-block inside its block
+        a0 = a1 = readlane64(my_addr, (sub + i) / TPB - first_blk) +
+                  (uint64_t)(((sub + i) % TPB) * sub_bytes);
       }
       nv0 = min(n_kv - t0, 16);
       nv1 = min(n_kv - t0 - 16, 16);
@@ -205,15 +205,15 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     KRegs<D> kc, kn;
     VRegs<D> vc;
     uint64_t a0, a1;
-    int o, nv0, nv1;
-    addr_of(0, a0, a1, o, nv0, nv1);
-    load_k<D, BS>(kc, a0, a1, o, nv0, nv1, g, r, qg);
+    int nv0, nv1;
+    addr_of(0, a0, a1, nv0, nv1);
+    load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
 #pragma unroll 1
     for (int i = 0; i < nt; ++i) {
-      load_v<D, BS>(vc, a0, a1, o, g, Hkv, r, qg);
+      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
       if (i + 1 < nt) {
-        addr_of(i + 1, a0, a1, o, nv0, nv1);
-        load_k<D, BS>(kn, a0, a1, o, nv0, nv1, g, r, qg);
+        addr_of(i + 1, a0, a1, nv0, nv1);
+        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
       }
       compute(kc, vc, sub + i);
       kc = kn;

@@ -251,12 +251,24 @@ __global__ __launch_bounds__(kCopyThreads) void scatter_kernel(XferArgs a, const
 }
 
 // ---- slot granularity: one token per unit -------------------------------------
-// Copy token `t` of a layer's block between the in-block layout
-// (K[Hkv][D/8][bs][8], V[Hkv][D][bs]) and a token-major record K[Hkv][D] | V[Hkv][D].
+// In-block layout: sub-blocks of sb = min(bs, 32) tokens, each K[Hkv][D/8][sb][8]
+// then V[Hkv][D][sb].  Returns the sub-block holding token t of the block and
+// leaves t's position inside it in `tt`.
+__device__ __forceinline__ char *token_sub_block(char *blk, uint32_t t, uint32_t Hkv, uint32_t D,
+                                                 uint32_t bs, uint32_t &sb, uint32_t &tt) {
+  sb = bs < 32u ? bs : 32u;
+  tt = t % sb;
+  return blk + (uint64_t)(t / sb) * ((uint64_t)2 * Hkv * sb * D * 2);
+}
+
+// Copy token `t` of a layer's block between the in-block layout and a
+// token-major record K[Hkv][D] | V[Hkv][D].
 // to_record = true gathers block -> record, false scatters record -> block.
 template <bool to_record>
 __device__ __forceinline__ void wg_copy_token(char *blk, char *rec, uint32_t t, uint32_t Hkv,
-                                              uint32_t D, uint32_t bs) {
+                                              uint32_t D, uint32_t bs_block) {
+  uint32_t bs;
+  blk = token_sub_block(blk, t, Hkv, D, bs_block, bs, t);
   const uint32_t n_chunks = Hkv * D / 8;  // K: 16-byte d-slices
   for (uint32_t c = threadIdx.x; c < n_chunks; c += blockDim.x) {
     u32x4 *in_blk = (u32x4 *)(blk + ((uint64_t)c * bs + t) * 16);
@@ -348,13 +360,14 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
     return;
   }
   const uint32_t t = (uint32_t)pos % a.bs;
-  char *blk = (char *)a.block_list[id] + a.layer_off;
+  uint32_t sb, tt;
+  char *blk = token_sub_block((char *)a.block_list[id] + a.layer_off, t, a.Hkv, a.D, a.bs, sb, tt);
   const uint32_t n_el = a.Hkv * a.D;
   const uint16_t *k = a.k_new + (int64_t)s * n_el, *v = a.v_new + (int64_t)s * n_el;
   for (uint32_t c = threadIdx.x; c < n_el / 8; c += blockDim.x)
-    *(u32x4 *)(blk + ((uint64_t)c * a.bs + t) * 16) = *(const u32x4 *)(k + (uint64_t)c * 8);
-  uint16_t *vblk = (uint16_t *)(blk + (uint64_t)a.Hkv * a.bs * a.D * 2);
-  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) vblk[(uint64_t)e * a.bs + t] = v[e];
+    *(u32x4 *)(blk + ((uint64_t)c * sb + tt) * 16) = *(const u32x4 *)(k + (uint64_t)c * 8);
+  uint16_t *vblk = (uint16_t *)(blk + (uint64_t)a.Hkv * sb * a.D * 2);
+  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) vblk[(uint64_t)e * sb + tt] = v[e];
   if (threadIdx.x == 0) {
     if (a.mark) {
       const int64_t u = a.units_per_block > 1 ? (int64_t)id * a.bs + t : id;

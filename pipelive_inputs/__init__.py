@@ -153,7 +153,7 @@ BF16_NAN = 0xFFFF  # poison pattern for unused slots and free blocks
 # --------------------------------------------------------------------------
 # in-block layouts (byte placement only; both consumers document the same
 # formulas independently)
-LAYOUT_D8 = 0   # K[Hkv][D/8][bs][8] then V[Hkv][D][bs]
+LAYOUT_D8 = 0   # runs of min(bs, 32) tokens, each K[Hkv][D/8][run][8] then V[Hkv][D][run]
 LAYOUT_ROW = 1  # K[Hkv][bs][D]      then V[Hkv][bs][D]
 
 
@@ -169,8 +169,14 @@ def token_slot_mask(layout: int, num_kv_heads: int, block_tokens: int, head_dim:
     hkv, bs, d = num_kv_heads, block_tokens, head_dim
     tok_bad = np.arange(bs) >= n_valid
     if layout == LAYOUT_D8:
-        k = np.broadcast_to(tok_bad[None, None, :, None], (hkv, d // 8, bs, 8))
-        v = np.broadcast_to(tok_bad[None, None, :], (hkv, d, bs))
+        # sub-blocks of min(bs, 32) tokens, each K[Hkv][D/8][sb][8] then V[Hkv][D][sb]
+        sb = min(bs, 32)
+        parts = []
+        for u in range(bs // sb):
+            bad = tok_bad[u * sb:(u + 1) * sb]
+            parts.append(np.broadcast_to(bad[None, None, :, None], (hkv, d // 8, sb, 8)).reshape(-1))
+            parts.append(np.broadcast_to(bad[None, None, :], (hkv, d, sb)).reshape(-1))
+        return np.concatenate(parts)
     elif layout == LAYOUT_ROW:
         k = np.broadcast_to(tok_bad[None, :, None], (hkv, bs, d))
         v = k

@@ -8,12 +8,18 @@ import pipelive_inputs as pin
 def pack_block(layout, k_tok, v_tok):
     """k_tok, v_tok: uint16 [bs][Hkv][D] (token-major logical content of one
     block) -> uint16 [blk_elems] in storage order.
-    layout 0: K as [Hkv][D/8][bs][8], V as [Hkv][D][bs];
+    layout 0: consecutive runs of min(bs, 32) tokens, each stored as K [Hkv][D/8][run][8]
+    followed by V [Hkv][D][run];
     layout 1: K and V as [Hkv][bs][D]."""
     bs, hkv, d = k_tok.shape
     if layout == 0:
-        k = k_tok.reshape(bs, hkv, d // 8, 8).transpose(1, 2, 0, 3)
-        v = v_tok.transpose(1, 2, 0)
+        run = min(bs, 32)
+        out = []
+        for lo in range(0, bs, run):
+            kk, vv = k_tok[lo:lo + run], v_tok[lo:lo + run]
+            out.append(np.ascontiguousarray(kk.reshape(run, hkv, d // 8, 8).transpose(1, 2, 0, 3)).reshape(-1))
+            out.append(np.ascontiguousarray(vv.transpose(1, 2, 0)).reshape(-1))
+        return np.concatenate(out)
     else:
         k = k_tok.transpose(1, 0, 2)
         v = v_tok.transpose(1, 0, 2)
@@ -24,8 +30,14 @@ def unpack_block(layout, blk, bs, hkv, d):
     """Inverse of pack_block -> (k_tok, v_tok) uint16 [bs][Hkv][D]."""
     half = hkv * bs * d
     if layout == 0:
-        k = blk[:half].reshape(hkv, d // 8, bs, 8).transpose(2, 0, 1, 3).reshape(bs, hkv, d)
-        v = blk[half:].reshape(hkv, d, bs).transpose(2, 0, 1)
+        run = min(bs, 32)
+        h = hkv * run * d
+        ks, vs = [], []
+        for i in range(bs // run):
+            part = blk[2 * h * i:2 * h * (i + 1)]
+            ks.append(part[:h].reshape(hkv, d // 8, run, 8).transpose(2, 0, 1, 3).reshape(run, hkv, d))
+            vs.append(part[h:].reshape(hkv, d, run).transpose(2, 0, 1))
+        k, v = np.concatenate(ks), np.concatenate(vs)
     else:
         k = blk[:half].reshape(hkv, bs, d).transpose(1, 0, 2)
         v = blk[half:].reshape(hkv, bs, d).transpose(1, 0, 2)

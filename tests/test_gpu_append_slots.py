@@ -38,7 +38,8 @@ def _cmp_patch(host, patch_h, patch_d, n_layers):
 
 
 @pytest.mark.parametrize("gran", [0, 1])
-@pytest.mark.parametrize("shape", [(4, 2, 64, 16), (32, 8, 128, 16), (16, 8, 128, 32)])
+@pytest.mark.parametrize("shape", [(4, 2, 64, 16), (32, 8, 128, 16), (16, 8, 128, 32), (16, 8, 128, 128),
+                                   (4, 2, 64, 64)])
 def test_append_then_decode_and_patch(gran, shape):
     Hq, Hkv, D, bs = shape
     rng = np.random.default_rng(17)

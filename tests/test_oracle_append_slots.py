@@ -17,11 +17,12 @@ def _region(gran, layout=0, L=2, B=24, bs=16, Hq=4, Hkv=2, D=64):
     return oracle.HostKV(L, Hq, Hkv, D, bs, B, layout=layout, dirty_gran=gran, fill_bits=pin.BF16_NAN)
 
 
+@pytest.mark.parametrize("bs", [16, 64])
 @pytest.mark.parametrize("layout", [0, 1])
 @pytest.mark.parametrize("gran", [0, 1])
-def test_append_builds_the_same_cache_as_dense_placement(layout, gran):
+def test_append_builds_the_same_cache_as_dense_placement(layout, gran, bs):
     rng = np.random.default_rng(3)
-    kv = _region(gran, layout)
+    kv = _region(gran, layout, bs=bs)
     S, steps = 3, 37
     table = np.array([[5, 9, 2, 14], [7, 0, 11, 15], [3, 4, 8, 16]], dtype=np.int32)
     start = np.array([0, 10, 16], dtype=np.int32)        # sequences 1, 2 already hold tokens (NaN here)
