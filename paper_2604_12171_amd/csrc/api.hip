@@ -252,12 +252,12 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
   p.G = p.Hq / p.Hkv;
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)kv->d.head_dim);
   p.scale_log2 = sc * 1.4426950408889634f;
-  // one wave per (sequence, KV head, block of QB query tokens); the ragged split is only
-  // known on the device, so launch the upper bound and let the surplus waves exit
-  const int qb = (kPrefillNQ * 16) / p.G;
-  const int64_t units = (int64_t)p.Hkv * ((total_q + qb - 1) / qb + num_seqs);
+  // one workgroup per (sequence, KV head, block of 4 * QB query tokens); the ragged split is only
+  // known on the device, so launch the upper bound and let the surplus workgroups exit
+  const int wb = 4 * ((kPrefillNQ * 16) / p.G);
+  const int64_t units = (int64_t)p.Hkv * ((total_q + wb - 1) / wb + num_seqs);
   if (units > (1ll << 30)) return PIPELIVE_E_INVAL;
-  p.num_waves = (int32_t)units;
+  p.num_units = (int32_t)units;
   p.num_blocks = kv->d.num_blocks;
   p.status = &dev_state(kv)->status;
   HIP_TRY(launch_attn_prefill(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));

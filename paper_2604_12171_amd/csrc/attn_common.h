@@ -18,6 +18,19 @@ __device__ __forceinline__ uint64_t readlane64(uint64_t v, int lane) {
   return ((uint64_t)hi << 32) | lo;
 }
 
+// max of a value with the lane 16 (32) positions away: one v_permlane16_swap
+// (v_permlane32_swap) of gfx950 instead of a trip through the LDS crossbar.
+// The swap of (x, x) leaves lane i's own value in one result and lane i^16's
+// (i^32's) in the other.
+__device__ __forceinline__ float xor16_max(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xor32_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));

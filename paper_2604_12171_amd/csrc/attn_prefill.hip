@@ -2,35 +2,78 @@
 // compute-bound stage (paper Sec. 2 "LLM Inference": prompt tokens are
 // processed in parallel) over the same block-list KV layout as decode.
 //
-// Work unit = (sequence, KV head, block of QB consecutive query tokens), one
-// per wave; the 4 waves of a workgroup take consecutive query blocks of the
-// same (sequence, KV head), so they stream the same K/V tiles at about the
-// same time and share them through the CU's cache.  A unit's NQ*16 score
-// columns are its QB tokens x the G query heads of the KV head (column =
-// token * G + head).  Per 32-token KV tile the wave computes S^T = K Q^T for
-// all columns with the K operand fetched once, applies the causal mask by
-// predicate, runs the online softmax per column and accumulates
-// O^T += V^T P^T with P split into two bf16 terms, the V operand again fetched
-// once for all columns.  The K operand of the next tile is in flight while the
-// current one is computed; V is loaded at the top of its own tile and lands
-// during the score/softmax phase.  NQ = 2 keeps the kernel at 250 VGPRs, so
-// two waves share a SIMD and one's softmax overlaps the other's MFMAs.
+// Work unit = (sequence, KV head, block of 4*QB consecutive query tokens), one
+// per workgroup; wave w of it owns the QB tokens [w*QB, (w+1)*QB) of the block.
+// A wave's NQ*16 score columns are its QB tokens x the G query heads of the KV
+// head (column = token * G + head).  The workgroup walks the 32-token KV tiles
+// that its last query may see; each tile's K and V of the KV head (two
+// contiguous runs of the in-block layout) are copied once from global memory
+// into a ring of LDS stages, two tiles ahead of the arithmetic, and all four
+// waves take their MFMA operands from there.  Per tile a wave computes
+// S^T = K Q^T for its columns, applies the causal mask by predicate, runs the
+// online softmax per column and accumulates O^T += V^T P^T with P split into
+// two bf16 terms.  A wave whose queries cannot see a tile, or that has no
+// queries at all, still takes part in the copies and barriers.
+#include <type_traits>
+
 #include "attn_common.h"
 
 namespace pipelive {
 namespace {
 
+// LDS image of one tile: the K run as in global memory, then the V rows padded
+// so that a wave's 8-byte reads (16 rows apart by lane) fall into distinct banks.
+template <int D, int BS>
+struct Stage {
+  static constexpr int SB = SubBlock<BS>::SB;           // tokens per contiguous run: 16 or 32
+  static constexpr int HALVES = kTile / SB;             // runs per tile: 2 or 1
+  static constexpr int KRUN = SB * D * 2;               // bytes of one K run (= one V run)
+  static constexpr int VROW = SB * 2;                   // bytes of one V row in global memory
+  static constexpr int VSTRIDE = VROW + 16;             // in LDS: 80 B (SB 32) or 48 B (SB 16)
+  static constexpr int VRUN = D * VSTRIDE;              // bytes of one V run in LDS
+  static constexpr int KBYTES = HALVES * KRUN;          // K of the tile
+  static constexpr int BYTES = KBYTES + HALVES * VRUN;  // whole stage
+  static constexpr int CHUNKS = 2 * HALVES * KRUN / 16; // 16-byte pieces copied per tile
+  static constexpr int PER_THREAD = CHUNKS / 256;       // 4 (D 128) or 2 (D 64)
+};
+
+#ifdef PIPELIVE_PREFILL_TRACE
+// development builds: shader-clock totals per phase, summed over the tiles of wave 0 of workgroup 0
+__device__ long long g_prefill_trace[16];
+#define PTRACE_DECL long long tr_t0 = 0; long long tr_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; const bool tr_on = blockIdx.x == 0 && tid < 64; const long long tr_c0 = clock64(), tr_w0 = wall_clock64()
+#define PTRACE_START() do { __builtin_amdgcn_sched_barrier(0); tr_t0 = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define PTRACE(k) do { __builtin_amdgcn_sched_barrier(0); const long long n_ = clock64(); tr_acc[k] += n_ - tr_t0; tr_t0 = n_; __builtin_amdgcn_sched_barrier(0); } while (0)
+#define PTRACE_FLUSH(ntiles) do { if (tr_on && lane == 0) { for (int i_ = 0; i_ < 8; ++i_) g_prefill_trace[i_] = tr_acc[i_]; g_prefill_trace[8] = (ntiles); g_prefill_trace[9] = clock64() - tr_c0; g_prefill_trace[10] = wall_clock64() - tr_w0; } } while (0)
+#else
+#define PTRACE_DECL do {} while (0)
+#define PTRACE_START() do {} while (0)
+#define PTRACE(k) do {} while (0)
+#define PTRACE_FLUSH(n) do {} while (0)
+#endif
+
+constexpr int kStages = 3;
+typedef u32x4 __attribute__((address_space(3))) *lds_u4;
+typedef u32x2 __attribute__((address_space(3))) *lds_u2;
+typedef char __attribute__((address_space(3))) *lds_ptr;
+
 template <int D, int BS, int NQ>
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
-  constexpr int NC = D / 32, ND = D / 16;
-  const int lane = threadIdx.x & 63;
-  const int gw = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * 4 + (threadIdx.x >> 6)));
+  using St = Stage<D, BS>;
+  constexpr int NC = D / 32, ND = D / 16, SB = St::SB;
+  __shared__ __attribute__((aligned(16))) char lds[kStages * St::BYTES];
+
+  const int tid = threadIdx.x;
+  PTRACE_DECL;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, qg = lane >> 4;
   const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
-  const int QB = (NQ * 16) / G;  // query tokens per unit
+  const int QB = (NQ * 16) / G;  // query tokens per wave
+  const int WB = 4 * QB;         // query tokens per workgroup
+  const int unit = blockIdx.x;
 
-  // ---- locate unit gw: units of sequence s = Hkv * ceil(q_len / QB), ordered (s, head, block)
-  int s = -1, nqb = 0;
+  // ---- locate the unit: units of sequence s = Hkv * ceil(q_len / WB), ordered (s, head, block)
+  int s = -1, nwb = 0;
   int64_t rem = 0;
   {
     int64_t carry = 0;
@@ -38,33 +81,42 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       const bool in = base + lane < S;
       int ql = 0;
       if (in) ql = p.q_offsets[base + lane + 1] - p.q_offsets[base + lane];
-      const int nb = ql > 0 ? (ql + QB - 1) / QB : 0;
+      const int nb = ql > 0 ? (ql + WB - 1) / WB : 0;
       const int units = nb * Hkv;
       const int inc = wave_inclusive_scan(units, lane);
-      const uint64_t bal = __ballot(in && carry + inc > gw);  // first sequence whose range holds gw
+      const uint64_t bal = __ballot(in && carry + inc > unit);  // first sequence whose range holds it
       if (bal) {
         const int k = __ffsll((long long)bal) - 1;
         s = base + k;
-        nqb = __builtin_amdgcn_readlane(nb, k);
-        rem = gw - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
+        nwb = __builtin_amdgcn_readlane(nb, k);
+        rem = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
       }
       carry += __builtin_amdgcn_readlane(inc, 63);
     }
   }
-  if (s < 0) return;  // beyond the last unit
+  if (s < 0) return;  // beyond the last unit (whole workgroup: the decision is the same in every wave)
   // later query blocks attend to more tokens: hand them out first so the launch ends evenly
-  const int g = (int)(rem / nqb), qb = nqb - 1 - (int)(rem % nqb);
+  const int g = (int)(rem / nwb), wb = nwb - 1 - (int)(rem % nwb);
   const int q0 = p.q_offsets[s], qlen = p.q_offsets[s + 1] - q0;
   int n = p.ctx[s];
   if (n > p.max_ctx) n = p.max_ctx;
   if (qlen > n) {  // more queries than cached tokens: flag and skip
-    if (lane == 0) atomicCAS(p.status, 0, PIPELIVE_E_INVAL);
+    if (tid == 0) atomicCAS(p.status, 0, PIPELIVE_E_INVAL);
     return;
   }
-  const int tok0 = qb * QB;                                // first query token of the unit
-  const int ntok = min(QB, qlen - tok0);                   // query tokens in this unit
-  const int pos0 = n - qlen + tok0;                        // position of the first query token
-  const int p_max = pos0 + ntok - 1;                       // last position any column attends to
+  // workgroup: the tiles its last query may see
+  const int wg_tok0 = wb * WB;
+  const int wg_ntok = min(WB, qlen - wg_tok0);
+  const int wg_pmax = n - qlen + wg_tok0 + wg_ntok - 1;
+  const int nt_wg = (wg_pmax + kTile) / kTile;
+  const int wg_nkv = wg_pmax + 1;
+  // wave: its own queries
+  const int tok0 = wg_tok0 + w * QB;
+  const int ntok = max(min(QB, qlen - tok0), 0);
+  const int pos0 = n - qlen + tok0;         // position of the wave's first query
+  const int p_max = pos0 + ntok - 1;        // last position any of its columns attends to
+  const int nt_w = ntok > 0 ? (p_max + kTile) / kTile : 0;
+  const int n_kv = p_max + 1;
 
   // per column block: validity, causal limit, Q^T operand
   int p_col[NQ];
@@ -84,7 +136,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       qreg[nq][c] = as_bf16x8(v);
     }
   }
-  const int p_min = pos0;  // smallest causal limit over the unit's columns (wave-uniform)
+  const int p_min = pos0;  // smallest causal limit over the wave's columns (wave-uniform)
 
   f32x4 acc[ND][NQ];
   float m[NQ], l[NQ];
@@ -96,12 +148,119 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     for (int c = 0; c < ND; ++c) acc[c][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  const int nt_all = (p_max + kTile) / kTile;  // KV tiles 0 .. nt_all-1 cover positions 0 .. p_max
-  const int n_kv = p_max + 1;                  // tokens this unit may read
+  // ---- block addresses, resolved 32 tiles at a time, one block per lane; the batch after the
+  // current one is resolved early so that the copies never wait for it
+  constexpr int TPB = BS >= kTile ? BS / kTile : 1;  // tiles per block (a 16-token block is half a tile)
+  const int n_blocks_seq = (wg_nkv + BS - 1) / BS;
+  const uint32_t sub_bytes = SubBlock<BS>::bytes(Hkv, D);
+  uint64_t addr_a = 0, addr_b = 0;  // this lane's block address in the batches held (even, odd)
+  uint32_t bad_bits = 0;            // bit 0 / 1: the even / odd batch has an invalid table entry
+  struct Resolved {
+    uint64_t addr;
+    uint32_t bad;
+  };
+  auto resolve = [&](int batch) -> Resolved {
+    Resolved out = {0, 0};
+    const int t_lo = batch * kSubTiles;
+    if (t_lo >= nt_wg) return out;
+    const int t_hi = min(t_lo + kSubTiles, nt_wg);  // exclusive
+    const int first_blk = BS < kTile ? t_lo * 2 : t_lo / TPB;
+    const int last_blk = BS < kTile ? t_hi * 2 - 1 : (t_hi - 1) / TPB;
+    const int nblk = min(last_blk + 1, n_blocks_seq) - first_blk;
+    bool bad = false;
+    if (lane < nblk) {
+      const int id = p.table[(int64_t)s * p.table_stride + first_blk + lane];
+      if ((uint32_t)id < (uint64_t)p.num_blocks) out.addr = p.block_list[id] + p.layer_off;
+      else bad = true;
+    }
+    if (__any(bad)) {  // never dereference a bad id: flag it and leave the batch's tokens out
+      if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
+      out.bad = 1;
+    }
+    return out;
+  };
+  auto resolve_into_slot = [&](int batch) {
+    const Resolved rv = resolve(batch);
+    if (batch & 1) {
+      addr_b = rv.addr;
+      bad_bits = (bad_bits & 1u) | (rv.bad << 1);
+    } else {
+      addr_a = rv.addr;
+      bad_bits = (bad_bits & 2u) | rv.bad;
+    }
+  };
+  // addresses of the two runs' sub-blocks of tile t (the same sub-block twice when SB = 32)
+  auto tile_addr = [&](int t, uint64_t &a0, uint64_t &a1, bool &bad) {
+    const int batch = t / kSubTiles, i = t % kSubTiles;
+    const uint64_t my = (batch & 1) ? addr_b : addr_a;
+    bad = (bad_bits >> (batch & 1)) & 1u;
+    if (BS < kTile) {
+      const int nblk = min((batch * kSubTiles + kSubTiles) * 2, n_blocks_seq) - batch * kSubTiles * 2;
+      a0 = readlane64(my, 2 * i);
+      a1 = (2 * i + 1 < nblk) ? readlane64(my, 2 * i + 1) : a0;
+    } else {
+      const int first_blk = batch * kSubTiles / TPB;
+      a0 = a1 = readlane64(my, t / TPB - first_blk) + (uint64_t)((t % TPB) * sub_bytes);
+    }
+  };
 
-  auto compute = [&](KRegs<D> &kc, VRegs<D> &vc, int tile) {
+  // ---- global -> registers -> LDS copy of one tile, 16 bytes x PER_THREAD per thread.
+  // Chunk j of a thread is piece tid + 256 j of the tile's runs (K runs first, then V runs); which
+  // run that is, the byte inside it and the LDS position are fixed per thread and computed once.
+  constexpr int RC = St::KRUN / 16;  // 16-byte pieces per run
+  u32x4 stg[St::PER_THREAD];
+  uint32_t src_off[St::PER_THREAD];  // byte offset from the run's sub-block address (head included)
+  int dst_off[St::PER_THREAD];       // byte offset inside the LDS stage
+  bool second_half[St::PER_THREAD];  // the run belongs to the tile's second 16-token half (SB = 16 only)
+#pragma unroll
+  for (int j = 0; j < St::PER_THREAD; ++j) {
+    stg[j] = (u32x4){0, 0, 0, 0};
+    const int ci = tid + 256 * j;
+    const int run = ci / RC, off = (ci % RC) * 16;
+    const int is_v = run / St::HALVES, half = run % St::HALVES;
+    second_half[j] = half != 0;
+    src_off[j] = (uint32_t)((is_v ? Hkv + g : g) * St::KRUN + off);
+    dst_off[j] = is_v ? St::KBYTES + half * St::VRUN + (off / St::VROW) * St::VSTRIDE + off % St::VROW
+                      : half * St::KRUN + off;
+  }
+  auto stage_load = [&](int t) {
+    uint64_t a0, a1;
+    bool bad;
+    tile_addr(t, a0, a1, bad);
+    if (bad) return;  // the batch is skipped by every wave: whatever the registers hold is never used
+#pragma unroll
+    for (int j = 0; j < St::PER_THREAD; ++j) {
+      uint64_t base = a0;
+      if (St::HALVES == 2) {
+        // with RC >= 256 the half is a constant of j; otherwise it is a constant of the thread
+        if (RC >= 256) base = ((256 * j / RC) % 2) ? a1 : a0;
+        else base = second_half[j] ? a1 : a0;
+      }
+      stg[j] = *(global_u4)(base + src_off[j]);
+    }
+  };
+  auto stage_store = [&](int t) {
+    lds_ptr st = (lds_ptr)lds + (t % kStages) * St::BYTES;
+#pragma unroll
+    for (int j = 0; j < St::PER_THREAD; ++j) *(lds_u4)(st + dst_off[j]) = stg[j];
+  };
+
+  // MASK = false: every column sees the whole tile and every token of it is readable, so neither
+  // the causal predicate nor the clearing of unreadable V is needed (all tiles below the diagonal).
+  auto compute = [&](int tile, auto mask_tag) {
+    constexpr bool MASK = decltype(mask_tag)::value;
+    lds_ptr st = (lds_ptr)lds + (tile % kStages) * St::BYTES;
     const int j0 = tile * kTile;
-    const bool need_mask = j0 + kTile - 1 > p_min;  // some column cannot see the whole tile
+    // K operand: lane (token r of half T, k-group qg) holds K[token][32c + 8qg .. +7]
+    u32x4 kreg[2][NC];
+#pragma unroll
+    for (int T = 0; T < 2; ++T) {
+      const int hb = (SB == kTile) ? 0 : T * St::KRUN;
+      const int toff = (SB == kTile) ? 16 * T : 0;
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        kreg[T][c] = *(lds_u4)(st + hb + ((qg + 4 * c) * SB + toff + r) * 16);
+    }
     u32x4 ph[NQ], pl[NQ];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
@@ -111,30 +270,35 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         sc[T] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NC; ++c)
-          sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kc.k[T][c]), qreg[nq][c], sc[T], 0, 0, 0);
+          sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[T][c]), qreg[nq][c], sc[T], 0, 0, 0);
       }
+      PTRACE(1 + 2 * nq);  // K read + QK of this column block
+      // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
       float x[8];
       float mloc = -INFINITY;
 #pragma unroll
       for (int T = 0; T < 2; ++T)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int j = j0 + 16 * T + 4 * qg + i;
-          const bool ok = !need_mask || j <= p_col[nq];  // by predicate: unused slots may hold NaN
-          const float v = ok ? sc[T][i] * p.scale_log2 : -INFINITY;
+          float v = sc[T][i];
+          if (MASK) {  // by predicate: unused slots may hold NaN
+            const int j = j0 + 16 * T + 4 * qg + i;
+            v = j <= p_col[nq] ? v : -INFINITY;
+          }
           x[4 * T + i] = v;
           mloc = fmaxf(mloc, v);
         }
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 16));
-      mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-      const float m_new = fmaxf(m[nq], mloc);
+      mloc = xor16_max(mloc);
+      mloc = xor32_max(mloc);
+      const float m_new = fmaxf(m[nq], mloc * p.scale_log2);  // m is kept in the scaled domain
       // a column that sees nothing of this tile keeps its state (m_new may still be -inf only before
       // its first visible token, which is in tile 0 for every column)
-      const float alpha = (m_new == -INFINITY) ? 1.0f : fast_exp2(m[nq] - m_new);
+      const float alpha = (MASK && m_new == -INFINITY) ? 1.0f : fast_exp2(m[nq] - m_new);
+      const float neg_m = (MASK && m_new == -INFINITY) ? 0.f : -m_new;
       float pv[8], psum = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        pv[i] = (x[i] == -INFINITY) ? 0.f : fast_exp2(x[i] - m_new);
+        pv[i] = fast_exp2(__builtin_fmaf(x[i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
         psum += pv[i];
       }
       l[nq] = l[nq] * alpha + psum;
@@ -144,81 +308,78 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         for (int c = 0; c < ND; ++c) acc[c][nq] *= alpha;
       }
       split_weights(pv, ph[nq], pl[nq]);
+      PTRACE(2 + 2 * nq);  // softmax of this column block
     }
-    // V of tokens past the readable range must be zero (0 * NaN is NaN)
+    // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 4qg..4qg+3 of each half];
+    // V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
+    uint64_t vmask[2] = {~0ull, ~0ull};
+    if (MASK) {
 #pragma unroll
-    for (int T = 0; T < 2; ++T) {
-      const int nv = kc.nvalid[T];
-      if (nv < 16) {
+      for (int T = 0; T < 2; ++T) {
+        const int nv = n_kv - j0 - 16 * T;
         const int keep = min(max(nv - 4 * qg, 0), 4);
-        const uint64_t mask = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
-#pragma unroll
-        for (int c = 0; c < ND; ++c) {
-          vc.v[c][T].x &= (uint32_t)mask;
-          vc.v[c][T].y &= (uint32_t)(mask >> 32);
-        }
+        vmask[T] = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
       }
     }
 #pragma unroll
     for (int c = 0; c < ND; ++c) {
-      const bf16x8 va = as_bf16x8((u32x4){vc.v[c][0].x, vc.v[c][0].y, vc.v[c][1].x, vc.v[c][1].y});
+      u32x2 v[2];
+#pragma unroll
+      for (int T = 0; T < 2; ++T) {
+        const int hb = St::KBYTES + ((SB == kTile) ? 0 : T * St::VRUN);
+        const int toff = (SB == kTile) ? 16 * T : 0;
+        v[T] = *(lds_u2)(st + hb + (16 * c + r) * St::VSTRIDE + (toff + 4 * qg) * 2);
+        if (MASK) {
+          v[T].x &= (uint32_t)vmask[T];
+          v[T].y &= (uint32_t)(vmask[T] >> 32);
+        }
+      }
+      const bf16x8 va = as_bf16x8((u32x4){v[0].x, v[0].y, v[1].x, v[1].y});
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
         acc[c][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(ph[nq]), acc[c][nq], 0, 0, 0);
         acc[c][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(pl[nq]), acc[c][nq], 0, 0, 0);
       }
     }
+    PTRACE(5);  // V read + PV
   };
 
-  for (int sub = 0; sub < nt_all; sub += kSubTiles) {
-    const int nt = min(nt_all - sub, kSubTiles);
-    constexpr int TPB = BS >= kTile ? BS / kTile : 1;  // tiles per block (a 16-token block is half a tile)
-    const int first_blk = BS < kTile ? sub * 2 : sub / TPB;
-    const int last_blk = BS < kTile ? (sub + nt) * 2 - 1 : (sub + nt - 1) / TPB;
-    const int nblk = min(last_blk + 1, (n_kv + BS - 1) / BS) - first_blk;
-    uint64_t my_addr = 0;
-    bool bad = false;
-    if (lane < nblk) {
-      const int id = p.table[(int64_t)s * p.table_stride + first_blk + lane];
-      if ((uint32_t)id < (uint64_t)p.num_blocks) my_addr = p.block_list[id] + p.layer_off;
-      else bad = true;
-    }
-    if (__any(bad)) {
-      if (bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
-      continue;
-    }
-    const uint32_t sub_bytes = SubBlock<BS>::bytes(Hkv, D);
-    auto addr_of = [&](int i, uint64_t &a0, uint64_t &a1, int &nv0, int &nv1) {
-      const int t0 = (sub + i) * kTile;
-      if (BS < kTile) {
-        a0 = readlane64(my_addr, 2 * i);
-        a1 = (2 * i + 1 < nblk) ? readlane64(my_addr, 2 * i + 1) : a0;
-      } else {  // the tile's 32-token sub-block inside its block
-        a0 = a1 = readlane64(my_addr, (sub + i) / TPB - first_blk) +
-                  (uint64_t)(((sub + i) % TPB) * sub_bytes);
-      }
-      nv0 = min(n_kv - t0, 16);
-      nv1 = min(n_kv - t0 - 16, 16);
-    };
-    // Two waves per SIMD overlap each other's loads and arithmetic; K of the next tile is
-    // requested before the current tile is computed, V is fetched tile by tile.
-    KRegs<D> kc, kn;
-    VRegs<D> vc;
-    uint64_t a0, a1;
-    int nv0, nv1;
-    addr_of(0, a0, a1, nv0, nv1);
-    load_k<D, BS>(kc, a0, a1, nv0, nv1, g, r, qg);
-#pragma unroll 1
-    for (int i = 0; i < nt; ++i) {
-      load_v<D, BS>(vc, a0, a1, g, Hkv, r, qg);
-      if (i + 1 < nt) {
-        addr_of(i + 1, a0, a1, nv0, nv1);
-        load_k<D, BS>(kn, a0, a1, nv0, nv1, g, r, qg);
-      }
-      compute(kc, vc, sub + i);
-      kc = kn;
-    }
+  // ---- the tile loop: copies run two tiles ahead of the arithmetic, one barrier per tile.
+  // Stage (t+2) % 3 was last read for tile t-1, which every wave left before the barrier that
+  // ended iteration t-1.
+  resolve_into_slot(0);
+  resolve_into_slot(1);
+  stage_load(0);
+  stage_store(0);
+  if (nt_wg > 1) {
+    stage_load(1);
+    stage_store(1);
   }
+  __syncthreads();
+  auto step = [&](int t, auto mask_tag) {
+    PTRACE_START();
+    const bool more = t + 2 < nt_wg;
+    if (more) stage_load(t + 2);
+    const int batch = t / kSubTiles;
+    const bool bad = (bad_bits >> (batch & 1)) & 1u;
+    // a quarter into a batch the slot of the batch before it is free: resolve the batch after it
+    if (t % kSubTiles == 8 && batch >= 1) resolve_into_slot(batch + 1);
+    PTRACE(0);  // issue of the copies
+    if (t < nt_w && !bad) compute(t, mask_tag);
+    if (more) stage_store(t + 2);
+    PTRACE(6);  // registers -> LDS (waits for the global loads)
+    __syncthreads();
+    PTRACE(7);  // barrier
+  };
+  // tiles wholly below the workgroup's first query need no mask in any wave; the few tiles on the
+  // diagonal take the masked form (two loops, so that each form is generated once)
+  const int nt_plain = min((n - qlen + wg_tok0 + 1) / kTile, nt_wg);
+#pragma unroll 1
+  for (int t = 0; t < nt_plain; ++t) step(t, std::false_type{});
+#pragma unroll 1
+  for (int t = nt_plain; t < nt_wg; ++t) step(t, std::true_type{});
+
+  PTRACE_FLUSH(nt_wg);
 
   // ---- normalise and store: lane (qg, r) holds O[column r of block nq][16c + 4qg + i]
 #pragma unroll
@@ -251,12 +412,17 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 
 template <int D, int BS>
 hipError_t launch_t(const PrefillParams &p, hipStream_t st) {
-  const unsigned grid = (unsigned)((p.num_waves + 3) / 4);
-  hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ>), dim3(grid), dim3(256), 0, st, p);
+  hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 
 }  // namespace
+
+#ifdef PIPELIVE_PREFILL_TRACE
+extern "C" int pipelive_dev_prefill_trace(long long *out16) {
+  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prefill_trace), 16 * sizeof(long long));
+}
+#endif
 
 hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st) {
 #define X(d, b) \

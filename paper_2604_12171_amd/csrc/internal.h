@@ -83,7 +83,7 @@ struct PrefillParams {
   int32_t num_seqs, max_ctx;
   int32_t Hq, Hkv, G;
   float scale_log2;
-  int32_t num_waves;
+  int32_t num_units;  // workgroups launched (an upper bound on the units)
   int64_t num_blocks;
   int32_t *status;
 };
