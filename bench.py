@@ -399,11 +399,20 @@ def main():
             num += float(((got - ref) ** 2).sum())
             den += float((ref.astype(np.float64) ** 2).sum())
         cpu_bytes = Lc * batch.total_tokens * cfg.token_bytes
+        # the same oracle on one thread, on the four shortest sequences of layer 0
+        short = np.argsort(batch.ctx_lens)[:4]
+        tc1 = time.perf_counter()
+        host.attn_decode(0, pin.q_bits(cfg, seed, 0)[short], tab[short], batch.ctx_lens[short], nthreads=1)
+        tc1 = time.perf_counter() - tc1
+        one_bytes = int(batch.ctx_lens[short].sum()) * cfg.token_bytes
         result["cpu_baseline"] = {
             "value": round(cpu_bytes / tc / 1e9, 4), "unit": "GB/s", "cores": ncores, "kind": "oracle",
             "sample": f"decode attention of layers 0..{Lc - 1} of {L} (all {S} sequences, all "
                       f"{cfg.num_q_heads} heads, {Lc * batch.total_tokens} token-layers), {tc:.2f} s wall on "
                       f"{ncores} threads",
+            "single_thread": {"value": round(one_bytes / tc1 / 1e9, 4), "unit": "GB/s",
+                              "sample": f"layer 0, the 4 shortest sequences ({int(batch.ctx_lens[short].sum())} tokens), "
+                                        f"{tc1:.2f} s"},
             "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_rel_l2": math.sqrt(num / den)}
     # ---------------- independently allocated, layer-stacked blocks: the same batch over a pool of
     # 2 MiB physical blocks (k = 4 layers x 128 tokens), decode, pointer-only shrink, real release

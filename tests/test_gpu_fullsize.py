@@ -65,12 +65,13 @@ def _sample_pairs(cfg, n_pairs, salt):
 class Stage:
     """Device region + tensors of one workload."""
 
-    def __init__(self, cfg, B, capacity=None, arenas=4):
+    def __init__(self, cfg, B, capacity=None, arenas=4, stack_k=1, backing="arena"):
         self.cfg, self.B = cfg, B
         self.cap = capacity or B
         self.batch = pin.draw_batch(cfg, SEED, num_blocks=B)
         self.region = P.KVRegion(cfg.num_layers, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
-                                 cfg.block_tokens, B, capacity_blocks=self.cap, arenas=arenas)
+                                 cfg.block_tokens, B, capacity_blocks=self.cap, arenas=arenas, stack_k=stack_k,
+                                 backing=backing)
         fill_live_blocks(self.region, cfg, self.batch, SEED, self.cap, poison_tail=True)
         self.table = torch.from_numpy(self.batch.table).cuda()
         self.ctx = torch.from_numpy(self.batch.ctx_lens).cuda()
@@ -124,6 +125,7 @@ def _resize_and_check(st, B_new, tag):
     remap_d = torch.full((st.region.num_blocks,), -9, dtype=torch.int32, device="cuda")
     rc_d, res_d = P.pipelive_kv_resize(st.region, B_new, [st.table], [st.used], remap_out=remap_d)
     assert rc_h == oracle.OK and rc_d == P.OK, (rc_h, rc_d)
+    st.region.sync_block_list()   # a per-block pool had its block list permuted on the device
     assert (res_d.n_live, res_d.n_moved, res_d.old_num_blocks, res_d.new_num_blocks) == tuple(int(x) for x in res_h)
     assert np.array_equal(remap_d.cpu().numpy(), remap_h)
     assert np.array_equal(st.table.cpu().numpy(), table_h)
@@ -324,4 +326,80 @@ def test_longctx8b_split_decode_resize_and_final_patch():
     for l in range(L):
         assert torch.equal(tgt.read_blocks(l, compact), st.region.read_blocks(l, live)), l
     del st, tgt, patch
+    torch.cuda.empty_cache()
+
+
+def test_stage8b_stacked_per_block_pool_decode_shrink_release():
+    """The 8B stage's batch over independently allocated 2 MiB blocks (k = 4 layers x 128 tokens), as in
+    bench.py's stacked leg: sampled attention against the oracle, a 20 % shrink that copies nothing and leaves
+    the outputs bit-identical, then the freed blocks really go back to the device."""
+    base = pin.CONFIGS["stage8b"]
+    cfg = pin.StageConfig("stage8b-stacked", base.num_layers, base.num_q_heads, base.num_kv_heads, base.head_dim,
+                          128, base.num_seqs, base.ctx_lo, base.ctx_hi)
+    ctx = pin.draw_ctx_lens(cfg, SEED)
+    n_live = int(((ctx.astype(np.int64) + 127) // 128).sum())
+    B = int(n_live * 1.5)
+    B_new = int(B * 0.8)
+    torch.cuda.empty_cache()
+    log(f"stage8b-stacked: B {B} -> {B_new}, live {n_live}, {B * 4 * 2 / 1024:.1f} GiB in 2 MiB blocks")
+    st = Stage(cfg, B, stack_k=4, backing="vmm")
+    assert st.region.phys_bytes == 2 << 20 and st.region.pool.allocated == 4 * B
+    before = st.check_attention(32, salt=6)
+    _resize_and_check(st, B_new, "pointer-only shrink")
+    after = {l: st.decode(l).cpu().numpy() for l in before}
+    for l in before:
+        assert np.array_equal(before[l].view(np.uint32), after[l].view(np.uint32)), l
+    torch.cuda.synchronize()
+    free0 = torch.cuda.mem_get_info()[0]
+    assert st.region.release_tail(B) == 4 * (B - B_new)
+    gained = torch.cuda.mem_get_info()[0] - free0
+    assert abs(gained - 4 * (B - B_new) * (2 << 20)) <= 64 << 20, gained
+    again = {l: st.decode(l).cpu().numpy() for l in before}
+    for l in before:
+        assert np.array_equal(before[l].view(np.uint32), again[l].view(np.uint32)), l
+    assert P.pipelive_kv_read_state(st.region).status == 0
+    del st
+    torch.cuda.empty_cache()
+
+
+def test_prefill_chunk_in_bench_configuration():
+    """bench.py's chunked-prefill case (16 sequences, a 512-token chunk on 4096 cached tokens, 8B-stage heads).
+    A prefill row is the decode of its token over the context it may see, so sampled rows are checked against
+    the oracle's *decode* attention on a context truncated at the row's position."""
+    base = pin.CONFIGS["stage8b"]
+    S, ctx_len, q_len = 16, 4096, 512
+    cfg = pin.StageConfig("chunk512_of_4096", 1, base.num_q_heads, base.num_kv_heads, base.head_dim,
+                          base.block_tokens, S, ctx_len, ctx_len)
+    batch = pin.draw_batch(cfg, SEED, pool_factor=1.25)
+    cap = batch.num_blocks
+    region = P.KVRegion(1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, cap, arenas=3)
+    fill_live_blocks(region, cfg, batch, SEED, cap, poison_tail=False)
+    tq = S * q_len
+    qb = pin.bf16_normal(pin.stream_key(SEED, pin.STREAM_Q), 0, tq * cfg.num_q_heads * cfg.head_dim)
+    qb = qb.reshape(tq, cfg.num_q_heads, cfg.head_dim)
+    q_d = torch.from_numpy(qb.view(np.int16)).cuda().view(torch.bfloat16)
+    out = torch.full((tq, cfg.num_q_heads, cfg.head_dim), float("nan"), dtype=torch.float32, device="cuda")
+    qo = torch.arange(0, (S + 1) * q_len, q_len, dtype=torch.int32, device="cuda")
+    P.pipelive_paged_attn_prefill(region, 0, q_d, out, torch.from_numpy(batch.table).cuda(),
+                                  torch.from_numpy(batch.ctx_lens).cuda(), qo, tq)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.isfinite(got).all()
+    worst = (0.0, 0.0)
+    for s in (0, 5, 11, 15):
+        u = int(batch.used[s])
+        host = oracle.HostKV(1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, u,
+                             layout=cfg.layout, arenas=2, fill_bits=pin.BF16_NAN)
+        for j in range(u):
+            host.block(0, j)[:] = pin.kv_block_bits(cfg, SEED, cap, 0, 0, int(batch.table[s, j]))
+        tab = np.arange(u, dtype=np.int32)[None, :]
+        for i in (0, 1, 31, 32, 255, 300, 510, 511):          # rows of the chunk, incl. both ends
+            pos = ctx_len - q_len + i                          # the row sees positions 0 .. pos
+            ref = host.attn_decode(0, qb[s * q_len + i][None], tab, np.array([pos + 1], dtype=np.int32))[0]
+            ma, rl = attn_errors(got[s * q_len + i], ref)
+            assert ma <= MAX_ABS and rl <= REL_L2, (s, i, ma, rl)
+            worst = (max(worst[0], ma), max(worst[1], rl))
+    log(f"  prefill: 32 sampled rows, worst max_abs {worst[0]:.2e} rel_l2 {worst[1]:.2e}")
+    assert P.pipelive_kv_read_state(region).status == 0
+    del region
     torch.cuda.empty_cache()
