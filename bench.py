@@ -363,11 +363,25 @@ def main():
             e1.record()
             torch.cuda.synchronize()
             pms = e0.elapsed_time(e1) / 10
+            # the chunk's write side (token-major K/V rows -> in-block layout), same launch pattern
+            pk = pq[:, :pcfg.num_kv_heads, :].contiguous()
+            for _ in range(2):
+                P.pipelive_kv_append_chunk(preg, 0, pk, pk, pt, pc, qo_d, tq, mark=False)
+            e2, e3 = ev(), ev()
+            e2.record()
+            for _ in range(10):
+                P.pipelive_kv_append_chunk(preg, 0, pk, pk, pt, pc, qo_d, tq, mark=False)
+            e3.record()
+            torch.cuda.synchronize()
+            ams = e2.elapsed_time(e3) / 10
+            abytes = 2 * 2 * tq * pcfg.num_kv_heads * pcfg.head_dim * 2   # K and V, read + write
             pairs = Sp * sum(ctxp - qlp + i + 1 for i in range(qlp))     # (query, visible key) pairs per head
             flops = pairs * pcfg.num_q_heads * 4 * pcfg.head_dim          # QK^T and PV, 2 flop per MAC
             pres[tag] = {"seqs": Sp, "ctx": ctxp, "q_len": qlp, "us": round(pms * 1e3, 1),
                          "TFLOPs": round(flops / pms / 1e9, 1),
-                         "frac_of_mfma_peak": round(flops / pms / 1e9 / MFMA_PEAK_TFLOPS, 4)}
+                         "frac_of_mfma_peak": round(flops / pms / 1e9 / MFMA_PEAK_TFLOPS, 4),
+                         "append_chunk_us": round(ams * 1e3, 1), "append_chunk_GBps": round(abytes / ams / 1e6, 1),
+                         "append_chunk_note": "same buffers every launch: they fit the last-level cache, not an HBM figure"}
             del preg, pq, pout
         result["prefill"] = {"bound": "mfma", "peak_TFLOPs": MFMA_PEAK_TFLOPS, "dtype": "bf16", **pres}
 
@@ -399,8 +413,8 @@ def main():
             num += float(((got - ref) ** 2).sum())
             den += float((ref.astype(np.float64) ** 2).sum())
         cpu_bytes = Lc * batch.total_tokens * cfg.token_bytes
-        # the same oracle on one thread, on the four shortest sequences of layer 0
-        short = np.argsort(batch.ctx_lens)[:4]
+        # the same oracle on one thread, on the 16 shortest sequences of layer 0
+        short = np.argsort(batch.ctx_lens)[:16]
         tc1 = time.perf_counter()
         host.attn_decode(0, pin.q_bits(cfg, seed, 0)[short], tab[short], batch.ctx_lens[short], nthreads=1)
         tc1 = time.perf_counter() - tc1
@@ -411,7 +425,7 @@ def main():
                       f"{cfg.num_q_heads} heads, {Lc * batch.total_tokens} token-layers), {tc:.2f} s wall on "
                       f"{ncores} threads",
             "single_thread": {"value": round(one_bytes / tc1 / 1e9, 4), "unit": "GB/s",
-                              "sample": f"layer 0, the 4 shortest sequences ({int(batch.ctx_lens[short].sum())} tokens), "
+                              "sample": f"layer 0, the 16 shortest sequences ({int(batch.ctx_lens[short].sum())} tokens), "
                                         f"{tc1:.2f} s"},
             "gpu_vs_oracle_max_abs": err, "gpu_vs_oracle_rel_l2": math.sqrt(num / den)}
     # ---------------- independently allocated, layer-stacked blocks: the same batch over a pool of

@@ -153,8 +153,8 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
 
 /* Chunked-prefill attention of ONE layer over the same KV layout (Sec. 2 "LLM
  * Inference": the prompt's tokens are processed in parallel; compute-bound).
- * The new chunk's K/V is already in the cache (pipelive_kv_append or the
- * caller's own writes).  Sequence s holds ctx_lens[s] cached tokens, of which
+ * The new chunk's K/V is already in the cache (pipelive_kv_append_chunk or
+ * the caller's own writes).  Sequence s holds ctx_lens[s] cached tokens, of which
  * the last q_len = q_offsets[s+1] - q_offsets[s] are the chunk; query row
  * q_offsets[s] + i sits at position ctx_lens[s] - q_len + i and attends to the
  * cached tokens 0 .. that position (causal).  q_len = 1 is a decode step.
@@ -329,6 +329,23 @@ int32_t pipelive_kv_append(pipelive_kv_t *kv, int32_t layer, const void *k_new, 
                            const int32_t *block_table, int32_t table_stride,
                            const int32_t *positions, int32_t num_seqs, int32_t mark,
                            int32_t count_tokens, void *stream);
+
+/* append_chunk: the write side of a prefill chunk for one layer (Sec. 2 "LLM
+ * Inference": the prompt's tokens are processed together and their K/V enter
+ * the cache; Sec. 6.1: what a step writes is flagged).  Same convention as
+ * pipelive_paged_attn_prefill: sequence s holds ctx_lens[s] tokens *including*
+ * the chunk, whose q_len = q_offsets[s+1] - q_offsets[s] tokens are rows
+ * q_offsets[s] .. of k_new / v_new (DEVICE bf16 [total_q][Hkv][D], 16-B
+ * aligned); row q_offsets[s] + i goes to position ctx_lens[s] - q_len + i.
+ * mark and count_tokens as for append (count_tokens adds total_q's written
+ * tokens).  A chunk longer than its context is skipped; a 32-token window with
+ * a block id out of range or a position beyond the table row sets the status
+ * word and is not written.  total_q is a HOST value (sizes the launch).
+ * Asynchronous. */
+int32_t pipelive_kv_append_chunk(pipelive_kv_t *kv, int32_t layer, const void *k_new, const void *v_new,
+                                 const int32_t *block_table, int32_t table_stride,
+                                 const int32_t *ctx_lens, const int32_t *q_offsets, int32_t num_seqs,
+                                 int32_t total_q, int32_t mark, int32_t count_tokens, void *stream);
 
 /* mark_dirty: B[id] <- 1 for the n unit ids in ids (DEVICE int32), and
  * n_acc += n_tokens (the tokens scheduled in that step).  Asynchronous. */

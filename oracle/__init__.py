@@ -73,6 +73,9 @@ def lib():
                                          C.c_void_p]
         L.orc_max_blocks.restype = C.c_int64
         L.orc_max_blocks.argtypes = [C.c_double, C.c_double, C.c_int64, C.c_double, C.c_double]
+        L.orc_kv_append_chunk.restype = C.c_int32
+        L.orc_kv_append_chunk.argtypes = [C.POINTER(_KV), C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                          C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32]
         L.orc_kv_utilization.restype = C.c_double
         L.orc_kv_utilization.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
         L.orc_stacked_block_tokens.restype = C.c_int64
@@ -223,6 +226,16 @@ class HostKV:
         pos = np.ascontiguousarray(positions, dtype=np.int32)
         return lib().orc_kv_append(C.byref(self.c), int(layer), _ptr(k), _ptr(v), _ptr(table), table.shape[1],
                                    _ptr(pos), len(pos), int(bool(mark)), int(bool(count_tokens)))
+
+    def append_chunk(self, layer, k_new, v_new, table, ctx_lens, q_offsets, mark=True, count_tokens=False) -> int:
+        """k_new, v_new: uint16 [total_q][Hkv][D]; ctx_lens int32 [S] (chunk included); q_offsets int32 [S+1]."""
+        k = np.ascontiguousarray(k_new, dtype=np.uint16)
+        v = np.ascontiguousarray(v_new, dtype=np.uint16)
+        table = np.ascontiguousarray(table, dtype=np.int32)
+        ctx = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        qo = np.ascontiguousarray(q_offsets, dtype=np.int32)
+        return lib().orc_kv_append_chunk(C.byref(self.c), int(layer), _ptr(k), _ptr(v), _ptr(table), table.shape[1],
+                                         _ptr(ctx), _ptr(qo), len(ctx), int(bool(mark)), int(bool(count_tokens)))
 
     def mark_dirty(self, ids, n_tokens) -> int:
         ids = np.ascontiguousarray(ids, dtype=np.int32)

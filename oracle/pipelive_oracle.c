@@ -435,6 +435,51 @@ int32_t orc_kv_append(orc_kv_t *kv, int32_t layer, const uint16_t *k_new, const 
   return ORC_OK;
 }
 
+/* The write side of a prefill chunk for one layer: sequence s holds ctx[s]
+ * tokens including the chunk; its q_len = q_offsets[s+1] - q_offsets[s] new
+ * tokens (rows q_offsets[s] .. of k_new / v_new, each [Hkv][D]) take the
+ * positions ctx[s] - q_len .. ctx[s] - 1, one after the other, exactly as
+ * q_len single-token appends would place them.  A chunk longer than its
+ * context, a position beyond the table row or a bad block id is an error and
+ * nothing is written. */
+int32_t orc_kv_append_chunk(orc_kv_t *kv, int32_t layer, const uint16_t *k_new, const uint16_t *v_new,
+                            const int32_t *table, int32_t table_stride, const int32_t *ctx,
+                            const int32_t *q_offsets, int32_t num_seqs, int32_t mark,
+                            int32_t count_tokens) {
+  if (!kv || layer < 0 || layer >= kv->num_layers) return ORC_E_INVAL;
+  const int Hkv = kv->num_kv_heads, D = kv->head_dim, bs = kv->block_tokens;
+  for (int s = 0; s < num_seqs; ++s) {
+    const int ql = q_offsets[s + 1] - q_offsets[s];
+    if (ql < 0 || ql > ctx[s]) return ORC_E_INVAL;
+    for (int i = 0; i < ql; ++i) {
+      const int pos = ctx[s] - ql + i;
+      if (pos / bs >= table_stride) return ORC_E_INVAL;
+      int32_t id = table[(int64_t)s * table_stride + pos / bs];
+      if (id < 0 || id >= kv->num_blocks) return ORC_E_RANGE;
+    }
+  }
+  uint64_t written = 0;
+  for (int s = 0; s < num_seqs; ++s) {
+    const int ql = q_offsets[s + 1] - q_offsets[s];
+    for (int i = 0; i < ql; ++i) {
+      const int pos = ctx[s] - ql + i;
+      const int64_t row = (int64_t)q_offsets[s] + i;
+      const int32_t id = table[(int64_t)s * table_stride + pos / bs];
+      const int t = pos % bs;
+      uint16_t *blk = (uint16_t *)layer_block(kv, layer, id);
+      for (int g = 0; g < Hkv; ++g)
+        for (int d = 0; d < D; ++d) {
+          blk[k_elem(kv, g, t, d)] = k_new[(row * Hkv + g) * D + d];
+          blk[v_elem(kv, g, t, d)] = v_new[(row * Hkv + g) * D + d];
+        }
+      if (mark) set_bit(kv->dirty_bitmap, kv->dirty_gran ? (int64_t)id * bs + t : id);
+      ++written;
+    }
+  }
+  if (count_tokens) kv->n_acc += written;
+  return ORC_OK;
+}
+
 /* MaxBlocks(i, L) = floor((M_i * u - L * W) / (L * P))  (Alg. 1, function MaxBlocks) */
 int64_t orc_max_blocks(double mem_bytes, double util, int64_t layers, double weight_bytes_per_layer,
                        double block_bytes_per_layer) {

@@ -27,7 +27,7 @@ MAX_TABLES = 8
 PATCH_MAGIC = 0x564B4C50
 
 EXPORTS = [
-    "pipelive_bitmap_bytes", "pipelive_kv_dirty_units", "pipelive_kv_append", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
+    "pipelive_bitmap_bytes", "pipelive_kv_dirty_units", "pipelive_kv_append", "pipelive_kv_append_chunk", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
     "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_prefill", "pipelive_paged_attn_workspace_bytes",
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
@@ -93,6 +93,8 @@ def load(path: str | None = None):
     L.pipelive_kv_dirty_units.argtypes = [i64, i32, i32]
     L.pipelive_kv_append.restype = i32
     L.pipelive_kv_append.argtypes = [vp, i32, vp, vp, vp, i32, vp, i32, i32, i32, vp]
+    L.pipelive_kv_append_chunk.restype = i32
+    L.pipelive_kv_append_chunk.argtypes = [vp, i32, vp, vp, vp, i32, vp, vp, i32, i32, i32, i32, vp]
     L.pipelive_kv_state_bytes.restype = sz
     L.pipelive_kv_state_bytes.argtypes = [i64]
     L.pipelive_kv_create.restype = i32
@@ -241,6 +243,16 @@ def pipelive_kv_append(kv: "KVRegion", layer, k_new, v_new, block_table, positio
     rc = load().pipelive_kv_append(kv.handle, int(layer), _p(k_new), _p(v_new), _p(block_table),
                                    int(block_table.shape[1]), _p(positions), int(positions.numel()),
                                    int(bool(mark)), int(bool(count_tokens)), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_kv_append_chunk(kv: "KVRegion", layer, k_new, v_new, block_table, ctx_lens, q_offsets, total_q,
+                             mark=True, count_tokens=False, check=True):
+    """k_new, v_new bf16 [total_q][Hkv][D]; ctx_lens int32 [S] (chunk included); q_offsets int32 [S+1] (device)."""
+    rc = load().pipelive_kv_append_chunk(kv.handle, int(layer), _p(k_new), _p(v_new), _p(block_table),
+                                         int(block_table.shape[1]), _p(ctx_lens), _p(q_offsets),
+                                         int(ctx_lens.shape[0]), int(total_q), int(bool(mark)),
+                                         int(bool(count_tokens)), _stream())
     return _check(rc) if check else rc
 
 

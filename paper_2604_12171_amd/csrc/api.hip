@@ -367,6 +367,21 @@ int32_t pipelive_kv_append(pipelive_kv_t *kv, int32_t layer, const void *k_new, 
   return PIPELIVE_OK;
 }
 
+int32_t pipelive_kv_append_chunk(pipelive_kv_t *kv, int32_t layer, const void *k_new, const void *v_new,
+                                 const int32_t *block_table, int32_t table_stride,
+                                 const int32_t *ctx_lens, const int32_t *q_offsets, int32_t num_seqs,
+                                 int32_t total_q, int32_t mark, int32_t count_tokens, void *stream) {
+  if (!kv || !k_new || !v_new || !block_table || !ctx_lens || !q_offsets) return PIPELIVE_E_INVAL;
+  if (layer < 0 || layer >= kv->d.num_layers) return PIPELIVE_E_RANGE;
+  if (num_seqs < 0 || total_q < 0 || table_stride <= 0 || !aligned(k_new, 16) || !aligned(v_new, 16))
+    return PIPELIVE_E_INVAL;
+  if (num_seqs == 0 || total_q == 0) return PIPELIVE_OK;
+  HIP_TRY(launch_append_chunk(kv, layer, (const uint16_t *)k_new, (const uint16_t *)v_new, block_table,
+                              table_stride, ctx_lens, q_offsets, num_seqs, total_q, mark, count_tokens,
+                              (hipStream_t)stream));
+  return PIPELIVE_OK;
+}
+
 int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, size_t capacity) {
   if (!kv || n_layers <= 0 || capacity < 64 + 256) return 0;
   const uint64_t per = 4 + (uint64_t)n_layers * kv->unit_bytes;

@@ -1,6 +1,7 @@
 // Device helpers shared by the decode and prefill attention kernels (gfx950).
 #pragma once
 #include "internal.h"
+#include "scan.h"
 
 namespace pipelive {
 
@@ -59,14 +60,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float o) {
   return (uint16_t)(u >> 16);
 }
 
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int t = __shfl_up(v, o);
-    if (lane >= o) v += t;
-  }
-  return v;
-}
 
 constexpr int kTile = 32;      // tokens per tile
 constexpr int kSubTiles = 32;  // tiles whose block addresses are resolved at once

@@ -136,7 +136,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       qreg[nq][c] = as_bf16x8(v);
     }
   }
-  const int p_min = pos0;  // smallest causal limit over the wave's columns (wave-uniform)
 
   f32x4 acc[ND][NQ];
   float m[NQ], l[NQ];

@@ -119,6 +119,10 @@ hipError_t launch_append(const pipelive_kv *kv, int32_t layer, const uint16_t *k
                          const uint16_t *v_new, const int32_t *table, int32_t table_stride,
                          const int32_t *positions, int32_t num_seqs, int32_t mark,
                          int32_t count_tokens, hipStream_t st);
+hipError_t launch_append_chunk(const pipelive_kv *kv, int32_t layer, const uint16_t *k_new,
+                               const uint16_t *v_new, const int32_t *table, int32_t table_stride,
+                               const int32_t *ctx, const int32_t *q_offsets, int32_t num_seqs,
+                               int32_t total_q, int32_t mark, int32_t count_tokens, hipStream_t st);
 hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
                           uint32_t max_blocks, uint64_t payload_offset, hipStream_t st);
 hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,

@@ -345,6 +345,150 @@ struct AppendArgs {
   DevState *st;
 };
 
+// ---- the write side of a prefill chunk: up to 32 consecutive tokens of one (sequence, KV head)
+// per workgroup.  The token-major input rows are read coalesced into LDS and written out in the
+// in-block layout with the token index fastest, so K leaves as 512-byte runs and V^T as 64-byte
+// rows instead of 16-byte and 2-byte pieces.
+struct AppendChunkArgs {
+  const uint64_t *block_list;  // the layer's group row
+  uint64_t layer_off;
+  int64_t num_blocks;
+  const uint16_t *k_new, *v_new;  // [total_q][Hkv][D]
+  const int32_t *table, *ctx, *q_offsets;
+  int32_t table_stride, num_seqs;
+  uint32_t Hkv, D, bs, units_per_block;
+  int32_t mark, count_tokens;
+  u64 *dirty;
+  DevState *st;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
+  constexpr int ROW = D * 2 + 16;  // LDS row of one token and head, padded against bank conflicts
+  constexpr int CH = D / 8;        // 16-byte pieces of a row
+  __shared__ __attribute__((aligned(16))) char lk[32 * ROW];
+  __shared__ __attribute__((aligned(16))) char lv[32 * ROW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int Hkv = (int)a.Hkv, S = a.num_seqs, bs = (int)a.bs;
+  const int g = blockIdx.x % Hkv;
+  const int unit = blockIdx.x / Hkv;
+
+  // ---- locate the unit: sequence s owns one unit per 32-token window that its chunk touches
+  int s = -1, wi = 0;
+  {
+    int carry = 0;
+    for (int base = 0; base < S && s < 0; base += 64) {
+      const bool in = base + lane < S;
+      int nwin = 0;
+      if (in) {
+        const int ql = a.q_offsets[base + lane + 1] - a.q_offsets[base + lane];
+        const int hi = a.ctx[base + lane], lo = hi - ql;
+        if (ql > 0 && lo >= 0) nwin = (hi - 1) / 32 - lo / 32 + 1;
+        // a chunk longer than its context has no place in the cache: flag it (once) and skip it
+        if (ql > hi && blockIdx.x == 0 && tid < 64) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
+      }
+      const int inc = wave_inclusive_scan(nwin, lane);
+      const uint64_t bal = __ballot(in && carry + inc > unit);
+      if (bal) {
+        const int k = __ffsll((long long)bal) - 1;
+        s = base + k;
+        wi = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(nwin, k));
+      }
+      carry += __builtin_amdgcn_readlane(inc, 63);
+    }
+  }
+  if (s < 0) return;  // beyond the last unit; the same decision in every wave
+  const int q0 = a.q_offsets[s], ql = a.q_offsets[s + 1] - q0;
+  const int pos_hi = a.ctx[s], pos_lo = pos_hi - ql;
+  const int w = pos_lo / 32 + wi;                    // window [32w, 32w + 32)
+  const int j_lo = max(32 * w, pos_lo), j_hi = min(32 * w + 32, pos_hi);
+  const int tt_lo = j_lo - 32 * w, tt_hi = j_hi - 32 * w;  // valid token offsets inside the window
+
+  // ---- the blocks of the window: one, or two 16-token blocks
+  const int sb = bs < 32 ? bs : 32;
+  const int halves = 32 / sb;
+  char *base_h[2] = {nullptr, nullptr};
+  int32_t id_h[2] = {-1, -1};
+  bool ok = true;
+  for (int h = 0; h < halves; ++h) {
+    const int first = 32 * w + h * sb;  // first token position of this half
+    if (first + sb <= j_lo || first >= j_hi) continue;  // no token of the chunk in it
+    const int bi = first / bs;
+    if (bi >= a.table_stride) {
+      if (tid == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
+      ok = false;
+      continue;
+    }
+    const int32_t id = a.table[(int64_t)s * a.table_stride + bi];
+    if (id < 0 || id >= a.num_blocks) {
+      if (tid == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_RANGE);
+      ok = false;
+      continue;
+    }
+    id_h[h] = id;
+    // the sub-block that holds this half: blocks above 32 tokens are runs of 32-token sub-blocks
+    base_h[h] = (char *)a.block_list[id] + a.layer_off +
+                (uint64_t)((first % bs) / sb) * ((uint64_t)2 * Hkv * sb * D * 2);
+  }
+  if (!ok) return;  // uniform: nothing of a window with a bad table entry is written
+
+  // ---- token-major rows -> LDS (coalesced: a row of one head is D * 2 contiguous bytes)
+  for (int e = tid; e < 32 * CH; e += 256) {
+    const int tt = e / CH, c = e % CH;
+    if (tt < tt_lo || tt >= tt_hi) continue;
+    const int64_t row = (int64_t)q0 + (32 * w + tt - pos_lo);
+    const uint64_t off = ((uint64_t)row * Hkv + g) * D + 8 * c;
+    *(u32x4 *)(lk + tt * ROW + c * 16) = *(const u32x4 *)(a.k_new + off);
+    *(u32x4 *)(lv + tt * ROW + c * 16) = *(const u32x4 *)(a.v_new + off);
+  }
+  __syncthreads();
+
+  // ---- K[D/8][sb][8]: 16-byte pieces, token index fastest
+  const uint32_t khead = (uint32_t)(sb * D * 2);
+  for (int e = tid; e < 32 * CH; e += 256) {
+    const int c = e / 32, tt = e % 32;
+    if (tt < tt_lo || tt >= tt_hi) continue;
+    char *dst = base_h[tt / sb] + (uint64_t)g * khead + (uint32_t)((c * sb + tt % sb) * 16);
+    *(u32x4 *)dst = *(const u32x4 *)(lk + tt * ROW + c * 16);
+  }
+  // ---- V[D][sb]: a thread owns row d and a run of 32 * D / 256 consecutive tokens
+  {
+    constexpr int TPT = 32 * D / 256;  // tokens per thread: 16 (D 128) or 8 (D 64)
+    const int d = tid % D, t0 = (tid / D) * TPT;
+    uint16_t vals[TPT];
+#pragma unroll
+    for (int i = 0; i < TPT; ++i) vals[i] = *(const uint16_t *)(lv + (t0 + i) * ROW + d * 2);
+    if (t0 < tt_hi && t0 + TPT > tt_lo) {
+      uint16_t *dst = (uint16_t *)(base_h[t0 / sb] + (uint64_t)(Hkv + g) * khead) + (uint32_t)(d * sb + t0 % sb);
+      if (t0 >= tt_lo && t0 + TPT <= tt_hi) {  // whole run inside the chunk: 16-byte stores
+#pragma unroll
+        for (int i = 0; i < TPT; i += 8) {
+          u32x4 pk;
+          pk.x = vals[i] | ((uint32_t)vals[i + 1] << 16);
+          pk.y = vals[i + 2] | ((uint32_t)vals[i + 3] << 16);
+          pk.z = vals[i + 4] | ((uint32_t)vals[i + 5] << 16);
+          pk.w = vals[i + 6] | ((uint32_t)vals[i + 7] << 16);
+          *(u32x4 *)(dst + i) = pk;
+        }
+      } else {  // the chunk begins or ends inside the run: tokens outside it keep their bytes
+#pragma unroll
+        for (int i = 0; i < TPT; ++i)
+          if (t0 + i >= tt_lo && t0 + i < tt_hi) dst[i] = vals[i];
+      }
+    }
+  }
+  // ---- dirty marks and the token count, once per window (by the workgroup of KV head 0)
+  if (g == 0) {
+    if (a.mark && tid >= tt_lo && tid < tt_hi) {
+      const int j = 32 * w + tid;
+      const int32_t id = id_h[tid / sb];
+      const int64_t u = a.units_per_block > 1 ? (int64_t)id * bs + j % bs : id;
+      atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
+    }
+    if (a.count_tokens && tid == 0) atomicAdd(&a.st->n_acc, (unsigned long long)(tt_hi - tt_lo));
+  }
+}
+
 // one workgroup per sequence: the new token's K and V of one layer
 __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
   const int s = blockIdx.x;
@@ -431,6 +575,39 @@ hipError_t launch_append(const pipelive_kv *kv, int32_t layer, const uint16_t *k
   a.dirty = (u64 *)kv->d.dirty_bitmap;
   a.st = dev_state(kv);
   hipLaunchKernelGGL(append_kernel, dim3(num_seqs), dim3(kCopyThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_append_chunk(const pipelive_kv *kv, int32_t layer, const uint16_t *k_new,
+                               const uint16_t *v_new, const int32_t *table, int32_t table_stride,
+                               const int32_t *ctx, const int32_t *q_offsets, int32_t num_seqs,
+                               int32_t total_q, int32_t mark, int32_t count_tokens, hipStream_t st) {
+  AppendChunkArgs a;
+  a.block_list = kv->d.block_list + (int64_t)(layer / kv->d.stack_k) * kv->d.capacity_blocks;
+  a.layer_off = (uint64_t)(layer % kv->d.stack_k) * kv->blk_bytes;
+  a.num_blocks = kv->d.num_blocks;
+  a.k_new = k_new;
+  a.v_new = v_new;
+  a.table = table;
+  a.ctx = ctx;
+  a.q_offsets = q_offsets;
+  a.table_stride = table_stride;
+  a.num_seqs = num_seqs;
+  a.Hkv = (uint32_t)kv->d.num_kv_heads;
+  a.D = (uint32_t)kv->d.head_dim;
+  a.bs = (uint32_t)kv->d.block_tokens;
+  a.units_per_block = (uint32_t)kv->units_per_block;
+  a.mark = mark;
+  a.count_tokens = count_tokens;
+  a.dirty = (u64 *)kv->d.dirty_bitmap;
+  a.st = dev_state(kv);
+  // a chunk of q tokens touches at most q / 32 + 2 windows; the surplus workgroups exit
+  const int64_t units = ((int64_t)total_q / 32 + 2 * (int64_t)num_seqs) * kv->d.num_kv_heads;
+  if (units > 0x7FFFFFFF) return hipErrorInvalidValue;
+  if (kv->d.head_dim == 128)
+    hipLaunchKernelGGL(append_chunk_kernel<128>, dim3((unsigned)units), dim3(256), 0, st, a);
+  else
+    hipLaunchKernelGGL(append_chunk_kernel<64>, dim3((unsigned)units), dim3(256), 0, st, a);
   return hipGetLastError();
 }
 

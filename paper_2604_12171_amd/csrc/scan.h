@@ -1,4 +1,4 @@
-// Workgroup-wide exclusive prefix sum for 1024 lanes (16 waves of 64).
+// Prefix sums: inclusive over one wave, exclusive over a workgroup of 1024 lanes (16 waves of 64).
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -6,6 +6,16 @@
 namespace pipelive {
 
 constexpr int kScanThreads = 1024;
+
+// inclusive prefix sum of `v` over the 64 lanes of a wave
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(v, o);
+    if (lane >= o) v += t;
+  }
+  return v;
+}
 
 // returns the exclusive prefix of `v` over threadIdx.x; *total = sum over the workgroup.
 // `sh` must hold 17 uint32_t of LDS.  Contains barriers: call from all lanes.

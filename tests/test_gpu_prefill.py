@@ -99,3 +99,66 @@ def test_prefill_errors():
     P.pipelive_paged_attn_prefill(dev, 0, q, out, t, c, qo, 12)
     assert P.pipelive_kv_read_state(dev).status == P.E_INVAL
     assert P.pipelive_paged_attn_prefill(dev, 3, q, out, t, c, qo, 12, check=False) == P.E_RANGE
+
+
+@pytest.mark.parametrize("gran", [0, 1])
+@pytest.mark.parametrize("shape", [(4, 2, 64, 16), (32, 8, 128, 16), (16, 8, 128, 32), (16, 8, 128, 128), (8, 2, 64, 64)])
+def test_chunk_append_matches_oracle_and_feeds_prefill(shape, gran):
+    """The write side of a chunk: ragged starts and ends, whole windows and partial ones, then the prefill
+    attention over what was written; every byte of both pools, the dirty bitmap and n_acc are compared."""
+    import oracle
+    from gpu_common import assert_pools_equal, bitmap_ids
+    Hq, Hkv, D, bs = shape
+    L, B = 2, 60
+    rng = np.random.default_rng(31)
+    host = oracle.HostKV(L, Hq, Hkv, D, bs, B, dirty_gran=gran, fill_bits=pin.BF16_NAN)
+    dev = P.KVRegion(L, Hq, Hkv, D, bs, B, dirty_granularity=gran, fill_bits=pin.BF16_NAN, arenas=4)
+    S = 6
+    per_seq = B // S
+    table = rng.permutation(B)[: S * per_seq].reshape(S, per_seq).astype(np.int32)
+    cap_tokens = per_seq * bs
+    done = np.zeros(S, dtype=np.int32)
+    table_d = torch.from_numpy(table).cuda()
+    for rnd, want in enumerate([[33, 1, 0, 64, 17, 31], [32, 40, 5, 1, 15, 70], [7, 90, 64, 3, 0, 33]]):
+        qlen = np.minimum(np.asarray(want, dtype=np.int32), cap_tokens - done)
+        ctx = done + qlen
+        qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
+        tq = int(qo[-1])
+        for layer in range(L):
+            k = pin.f32_to_bf16_bits(rng.standard_normal((tq, Hkv, D)).astype(np.float32))
+            v = pin.f32_to_bf16_bits(rng.standard_normal((tq, Hkv, D)).astype(np.float32))
+            assert host.append_chunk(layer, k, v, table, ctx, qo, mark=True, count_tokens=(layer == 0)) == oracle.OK
+            P.pipelive_kv_append_chunk(dev, layer, torch.from_numpy(k.view(np.int16)).cuda().view(torch.bfloat16),
+                                       torch.from_numpy(v.view(np.int16)).cuda().view(torch.bfloat16), table_d,
+                                       torch.from_numpy(ctx).cuda(), torch.from_numpy(qo).cuda(), tq,
+                                       mark=True, count_tokens=(layer == 0))
+        torch.cuda.synchronize()
+        units = B * (bs if gran else 1)
+        assert np.array_equal(bitmap_ids(dev.dirty, units), host.dirty_ids()), rnd
+        st = P.pipelive_kv_read_state(dev)
+        assert st.n_acc == host.n_acc and st.status == 0
+        assert_pools_equal(host, dev, range(L), range(B))
+        # prefill attention of the chunk over the cache it just extended
+        q = pin.f32_to_bf16_bits(rng.standard_normal((tq, Hq, D)).astype(np.float32))
+        out = torch.full((tq, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+        P.pipelive_paged_attn_prefill(dev, 1, torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16), out,
+                                      table_d, torch.from_numpy(ctx).cuda(), torch.from_numpy(qo).cuda(), tq)
+        torch.cuda.synchronize()
+        ref = host.attn_prefill(1, q, table, ctx, qo, nthreads=8)
+        ma, rl = attn_errors(out.cpu().numpy(), ref)
+        assert ma <= MAX_ABS and rl <= REL_L2, (rnd, ma, rl)
+        done = ctx
+
+
+def test_chunk_append_flags_bad_input_and_skips_it():
+    dev = P.KVRegion(1, 4, 2, 64, 16, 12, fill_bits=pin.BF16_NAN)
+    k = torch.zeros((40, 2, 64), dtype=torch.bfloat16, device="cuda")
+    table = torch.tensor([[1, 99, 3]], dtype=torch.int32, device="cuda")      # second block id out of range
+    qo = torch.tensor([0, 40], dtype=torch.int32, device="cuda")
+    P.pipelive_kv_append_chunk(dev, 0, k, k, table, torch.tensor([40], dtype=torch.int32, device="cuda"), qo, 40)
+    assert P.pipelive_kv_read_state(dev).status == P.E_RANGE
+    assert (dev.block(0, 1).cpu().numpy().view(np.uint16) == pin.BF16_NAN).all()      # shares a window with the bad id
+    assert (dev.block(0, 3).cpu().numpy().view(np.uint16) == 0).any()                 # the next window was written
+    P.pipelive_kv_clear_status(dev)
+    P.pipelive_kv_append_chunk(dev, 0, k, k, table, torch.tensor([30], dtype=torch.int32, device="cuda"), qo, 40)
+    assert P.pipelive_kv_read_state(dev).status == P.E_INVAL                       # chunk longer than its context

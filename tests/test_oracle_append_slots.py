@@ -157,3 +157,44 @@ def test_slot_session_converges_and_resize_sees_pending_slots():
             kd, vd = gather_logical(dst, l, table[s], int(lens[s]))
             assert np.array_equal(ks, kd) and np.array_equal(vs, vd)
     assert (dst.block(0, 31) == pin.BF16_NAN).any()          # slots never written stay untouched
+
+
+@pytest.mark.parametrize("bs", [16, 32, 64])
+@pytest.mark.parametrize("gran", [0, 1])
+def test_chunk_append_equals_token_by_token_append(gran, bs):
+    """A prefill chunk lands exactly where the same tokens appended one at a time would (the single-token
+    append is pinned against dense placement above); the dirty set and n_acc agree as well."""
+    rng = np.random.default_rng(9)
+    a, b = _region(gran, 0, B=40, bs=bs), _region(gran, 0, B=40, bs=bs)
+    S = 4
+    table = rng.permutation(40)[: S * 8].reshape(S, 8).astype(np.int32)
+    ctx = np.array([37, 5, 0, 3 * bs], dtype=np.int32)        # context lengths including the chunk
+    qlen = np.array([20, 5, 0, bs + 1], dtype=np.int32)       # unaligned start, whole context, nothing, block + 1
+    qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
+    for layer in range(2):
+        k, v = _bits(rng, (int(qo[-1]), a.Hkv, a.D)), _bits(rng, (int(qo[-1]), a.Hkv, a.D))
+        assert a.append_chunk(layer, k, v, table, ctx, qo, mark=True, count_tokens=(layer == 0)) == oracle.OK
+        for i in range(int(qlen.max())):
+            pos = np.where(i < qlen, ctx - qlen + i, -1).astype(np.int32)
+            rows = np.minimum(qo[:-1] + i, int(qo[-1]) - 1)
+            assert b.append(layer, k[rows], v[rows], table, pos, mark=True, count_tokens=(layer == 0)) == oracle.OK
+    assert a.n_acc == b.n_acc == int(qlen.sum())
+    assert np.array_equal(a.dirty, b.dirty) and len(a.dirty_ids()) > 0
+    for layer in range(2):
+        for blk in range(40):
+            assert np.array_equal(a.block(layer, blk), b.block(layer, blk)), (layer, blk)
+
+
+def test_chunk_append_errors_leave_state_untouched():
+    kv = _region(1, 0, B=8)
+    rng = np.random.default_rng(1)
+    before = [kv.block(0, b).copy() for b in range(8)]
+    k, v = _bits(rng, (6, kv.Hkv, kv.D)), _bits(rng, (6, kv.Hkv, kv.D))
+    table = np.array([[1, 2, 3]], dtype=np.int32)
+    qo = np.array([0, 6], dtype=np.int32)
+    assert kv.append_chunk(0, k, v, table, np.array([5], np.int32), qo) == oracle.E_INVAL       # chunk longer than context
+    assert kv.append_chunk(0, k, v, table, np.array([50], np.int32), qo) == oracle.E_INVAL      # beyond the table row
+    assert kv.append_chunk(0, k, v, np.array([[1, 9, 3]], np.int32), np.array([20], np.int32), qo) == oracle.E_RANGE
+    assert kv.n_acc == 0 and len(kv.dirty_ids()) == 0
+    for b in range(8):
+        assert np.array_equal(kv.block(0, b), before[b])
