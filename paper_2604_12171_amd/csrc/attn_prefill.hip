@@ -8,8 +8,9 @@
 // head (column = token * G + head).  The workgroup walks the 32-token KV tiles
 // that its last query may see; each tile's K and V of the KV head (two
 // contiguous runs of the in-block layout) are copied once from global memory
-// into a ring of LDS stages, two tiles ahead of the arithmetic, and all four
-// waves take their MFMA operands from there.  Per tile a wave computes
+// into a ring of three LDS stages by LDS-direct loads (global_load_lds_dwordx4:
+// no staging registers), issued two tiles ahead of the arithmetic, and all
+// four waves take their MFMA operands from there.  Per tile a wave computes
 // S^T = K Q^T for its columns, applies the causal mask by predicate, runs the
 // online softmax per column and accumulates O^T += V^T P^T with P split into
 // two bf16 terms.  A wave whose queries cannot see a tile, or that has no
@@ -21,16 +22,20 @@
 namespace pipelive {
 namespace {
 
-// LDS image of one tile: the K run as in global memory, then the V rows padded
-// so that a wave's 8-byte reads (16 rows apart by lane) fall into distinct banks.
+// LDS image of one tile: the K runs as in global memory, then the V runs with the 16-byte pieces of
+// every row permuted (piece k of row d sits at position k ^ swizzle(d)), so that a wave's 8-byte
+// reads, 16 rows apart by lane, fall into distinct banks.  The image has no holes: the copies are
+// LDS-direct loads, which write 64 consecutive pieces per wave instruction.
 template <int D, int BS>
 struct Stage {
   static constexpr int SB = SubBlock<BS>::SB;           // tokens per contiguous run: 16 or 32
   static constexpr int HALVES = kTile / SB;             // runs per tile: 2 or 1
   static constexpr int KRUN = SB * D * 2;               // bytes of one K run (= one V run)
   static constexpr int VROW = SB * 2;                   // bytes of one V row in global memory
-  static constexpr int VSTRIDE = VROW + 16;             // in LDS: 80 B (SB 32) or 48 B (SB 16)
-  static constexpr int VRUN = D * VSTRIDE;              // bytes of one V run in LDS
+  static constexpr int CPR = VROW / 16;                 // 16-byte pieces per V row: 4 or 2
+  static constexpr int VRUN = D * VROW;                 // bytes of one V run (= KRUN)
+  // rows d and d + 4 (SB 32) or d + 8 (SB 16) would share banks: their pieces are rotated apart
+  __device__ static int swizzle(int d) { return SB == 32 ? (d >> 2) & 3 : (d >> 3) & 1; }
   static constexpr int KBYTES = HALVES * KRUN;          // K of the tile
   static constexpr int BYTES = KBYTES + HALVES * VRUN;  // whole stage
   static constexpr int CHUNKS = 2 * HALVES * KRUN / 16; // 16-byte pieces copied per tile
@@ -179,7 +184,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     return out;
   };
   auto resolve_into_slot = [&](int batch) {
-    const Resolved rv = resolve(batch);
+    Resolved rv = resolve(batch);
+    // use the address here, so that the wait for its load is placed here (once per 32 tiles) and not
+    // in front of every later read of it, where it would also wait for the tile copies in flight
+    asm volatile("" : "+v"(rv.addr));
     if (batch & 1) {
       addr_b = rv.addr;
       bad_bits = (bad_bits & 1u) | (rv.bad << 1);
@@ -203,30 +211,31 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     }
   };
 
-  // ---- global -> registers -> LDS copy of one tile, 16 bytes x PER_THREAD per thread.
-  // Chunk j of a thread is piece tid + 256 j of the tile's runs (K runs first, then V runs); which
-  // run that is, the byte inside it and the LDS position are fixed per thread and computed once.
+  // ---- global -> LDS copy of one tile: PER_THREAD LDS-direct loads per wave, each writing the 64
+  // consecutive 16-byte pieces [256 j + 64 w, +64) of the stage.  Which global piece a lane fetches
+  // for its position (the run, the byte inside it, for V the un-permuted piece) is fixed per thread.
   constexpr int RC = St::KRUN / 16;  // 16-byte pieces per run
-  u32x4 stg[St::PER_THREAD];
   uint32_t src_off[St::PER_THREAD];  // byte offset from the run's sub-block address (head included)
-  int dst_off[St::PER_THREAD];       // byte offset inside the LDS stage
   bool second_half[St::PER_THREAD];  // the run belongs to the tile's second 16-token half (SB = 16 only)
 #pragma unroll
   for (int j = 0; j < St::PER_THREAD; ++j) {
-    stg[j] = (u32x4){0, 0, 0, 0};
-    const int ci = tid + 256 * j;
-    const int run = ci / RC, off = (ci % RC) * 16;
+    const int ci = tid + 256 * j;  // position in the stage
+    const int run = ci / RC, q = ci % RC;
     const int is_v = run / St::HALVES, half = run % St::HALVES;
     second_half[j] = half != 0;
+    int off = q * 16;
+    if (is_v) {
+      const int d = q / St::CPR, pos = q % St::CPR;
+      off = d * St::VROW + ((pos ^ St::swizzle(d)) * 16);
+    }
     src_off[j] = (uint32_t)((is_v ? Hkv + g : g) * St::KRUN + off);
-    dst_off[j] = is_v ? St::KBYTES + half * St::VRUN + (off / St::VROW) * St::VSTRIDE + off % St::VROW
-                      : half * St::KRUN + off;
   }
   auto stage_load = [&](int t) {
     uint64_t a0, a1;
     bool bad;
     tile_addr(t, a0, a1, bad);
-    if (bad) return;  // the batch is skipped by every wave: whatever the registers hold is never used
+    if (bad) return;  // the batch is skipped by every wave: whatever the stage holds is never used
+    lds_ptr st = (lds_ptr)lds + (t % kStages) * St::BYTES + w * 1024;
 #pragma unroll
     for (int j = 0; j < St::PER_THREAD; ++j) {
       uint64_t base = a0;
@@ -235,13 +244,22 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         if (RC >= 256) base = ((256 * j / RC) % 2) ? a1 : a0;
         else base = second_half[j] ? a1 : a0;
       }
-      stg[j] = *(global_u4)(base + src_off[j]);
+      __builtin_amdgcn_global_load_lds((global_u4)(base + src_off[j]), (lds_u4)(st + 4096 * j), 16, 0, 0);
     }
   };
-  auto stage_store = [&](int t) {
-    lds_ptr st = (lds_ptr)lds + (t % kStages) * St::BYTES;
-#pragma unroll
-    for (int j = 0; j < St::PER_THREAD; ++j) *(lds_u4)(st + dst_off[j]) = stg[j];
+  // The barrier that ends a tile: this wave's copies of the next tile have landed and its LDS reads of
+  // the current one are done; the copies of the tile after next, issued a moment ago, may still be
+  // in flight (a plain __syncthreads() would wait for them too and halve the prefetch distance).
+  auto tile_barrier = [&](bool newest_tile_in_flight) {
+    asm volatile("" ::: "memory");
+    if (newest_tile_in_flight) {
+      if (St::PER_THREAD == 4) __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
+      else __builtin_amdgcn_s_waitcnt(0x0072);                      // vmcnt(2) lgkmcnt(0)
+    } else {
+      __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
   };
 
   // MASK = false: every column sees the whole tile and every token of it is readable, so neither
@@ -326,8 +344,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
       for (int T = 0; T < 2; ++T) {
         const int hb = St::KBYTES + ((SB == kTile) ? 0 : T * St::VRUN);
-        const int toff = (SB == kTile) ? 16 * T : 0;
-        v[T] = *(lds_u2)(st + hb + (16 * c + r) * St::VSTRIDE + (toff + 4 * qg) * 2);
+        const int tb = ((SB == kTile ? 16 * T : 0) + 4 * qg) * 2;  // byte of the lane's 4 tokens inside row d
+        // swizzle(16 c + r) depends on r alone: a lane constant
+        v[T] = *(lds_u2)(st + hb + (16 * c + r) * St::VROW + (((tb / 16) ^ St::swizzle(r)) * 16) + tb % 16);
         if (MASK) {
           v[T].x &= (uint32_t)vmask[T];
           v[T].y &= (uint32_t)(vmask[T] >> 32);
@@ -343,18 +362,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     PTRACE(5);  // V read + PV
   };
 
-  // ---- the tile loop: copies run two tiles ahead of the arithmetic, one barrier per tile.
-  // Stage (t+2) % 3 was last read for tile t-1, which every wave left before the barrier that
-  // ended iteration t-1.
+  // ---- the tile loop: copies are issued two tiles ahead of the arithmetic and need to have landed
+  // one tile ahead, one barrier per tile.  Stage (t+2) % 3 was last read for tile t-1, which every
+  // wave left before the barrier that ended iteration t-1.
   resolve_into_slot(0);
   resolve_into_slot(1);
   stage_load(0);
-  stage_store(0);
-  if (nt_wg > 1) {
-    stage_load(1);
-    stage_store(1);
-  }
-  __syncthreads();
+  if (nt_wg > 1) stage_load(1);
+  tile_barrier(false);
   auto step = [&](int t, auto mask_tag) {
     PTRACE_START();
     const bool more = t + 2 < nt_wg;
@@ -365,10 +380,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     if (t % kSubTiles == 8 && batch >= 1) resolve_into_slot(batch + 1);
     PTRACE(0);  // issue of the copies
     if (t < nt_w && !bad) compute(t, mask_tag);
-    if (more) stage_store(t + 2);
-    PTRACE(6);  // registers -> LDS (waits for the global loads)
-    __syncthreads();
-    PTRACE(7);  // barrier
+    PTRACE(6);
+    tile_barrier(more);  // tile t+1 must be in LDS past the barrier; the copies of tile t+2 may still fly
+    PTRACE(7);           // wait for the copies + barrier
   };
   // tiles wholly below the workgroup's first query need no mask in any wave; the few tiles on the
   // diagonal take the masked form (two loops, so that each form is generated once)
