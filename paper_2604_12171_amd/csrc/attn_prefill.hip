@@ -57,6 +57,7 @@ __device__ long long g_prefill_trace[16];
 #endif
 
 constexpr int kStages = 3;
+constexpr float kLazyMaxStep = 8.0f;  // log2 of the growth of a column's maximum that triggers a rescale
 typedef u32x4 __attribute__((address_space(3))) *lds_u4;
 typedef u32x2 __attribute__((address_space(3))) *lds_u2;
 typedef char __attribute__((address_space(3))) *lds_ptr;
@@ -143,11 +144,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   }
 
   f32x4 acc[ND][NQ];
-  float m[NQ], l[NQ];
+  f32x4 lacc[NQ];  // every element: the column's running denominator
+  float m[NQ];
+  const bf16x8 ones = as_bf16x8((u32x4){0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     m[nq] = -INFINITY;
-    l[nq] = 0.f;
+    lacc[nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int c = 0; c < ND; ++c) acc[c][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
@@ -307,23 +310,25 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         }
       mloc = xor16_max(mloc);
       mloc = xor32_max(mloc);
-      const float m_new = fmaxf(m[nq], mloc * p.scale_log2);  // m is kept in the scaled domain
-      // a column that sees nothing of this tile keeps its state (m_new may still be -inf only before
-      // its first visible token, which is in tile 0 for every column)
-      const float alpha = (MASK && m_new == -INFINITY) ? 1.0f : fast_exp2(m[nq] - m_new);
-      const float neg_m = (MASK && m_new == -INFINITY) ? 0.f : -m_new;
-      float pv[8], psum = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        pv[i] = fast_exp2(__builtin_fmaf(x[i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
-        psum += pv[i];
-      }
-      l[nq] = l[nq] * alpha + psum;
-      m[nq] = m_new;
-      if (__any(alpha != 1.0f)) {
+      // m is kept in the scaled domain and only follows the running maximum when that has grown by
+      // more than 2^8: until then the weights are taken against the older reference (they stay below
+      // 2^8, harmless in fp32 sums and in the bf16 pair) and the accumulators need no rescaling.  The
+      // common factor cancels in O / l, so the result is the same softmax.
+      const float m_seen = fmaxf(m[nq], mloc * p.scale_log2);
+      if (__any(m_seen - m[nq] > kLazyMaxStep)) {  // rare after the first tiles; -inf -> finite counts as growth
+        const float m_new = (m_seen - m[nq] > kLazyMaxStep) ? m_seen : m[nq];
+        // a column that has seen nothing yet (m_new still -inf, masked tiles only) keeps its state
+        const float alpha = (m_new == -INFINITY) ? 1.0f : fast_exp2(m[nq] - m_new);
+        m[nq] = m_new;
+        lacc[nq] *= alpha;
 #pragma unroll
         for (int c = 0; c < ND; ++c) acc[c][nq] *= alpha;
       }
+      const float neg_m = (MASK && m[nq] == -INFINITY) ? 0.f : -m[nq];
+      float pv[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        pv[i] = fast_exp2(__builtin_fmaf(x[i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
       split_weights(pv, ph[nq], pl[nq]);
       PTRACE(2 + 2 * nq);  // softmax of this column block
     }
@@ -337,6 +342,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         const int keep = min(max(nv - 4 * qg, 0), 4);
         vmask[T] = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
       }
+    }
+    // the denominators: sum over the tile's tokens of the same bf16 pairs, as one more row of V^T
+    // that holds ones (every row of the 16 x 16 result is that sum: no cross-lane reduction later)
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(ph[nq]), lacc[nq], 0, 0, 0);
+      lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(pl[nq]), lacc[nq], 0, 0, 0);
     }
 #pragma unroll
     for (int c = 0; c < ND; ++c) {
@@ -397,9 +409,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   // ---- normalise and store: lane (qg, r) holds O[column r of block nq][16c + 4qg + i]
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
-    float lt = l[nq];
-    lt += __shfl_xor(lt, 16);
-    lt += __shfl_xor(lt, 32);
+    const float lt = lacc[nq][0];
     if (!col_ok[nq]) continue;
     const int col = nq * 16 + r;
     const int ti = col / G, hh = col % G;
