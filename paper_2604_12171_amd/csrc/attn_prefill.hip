@@ -59,7 +59,6 @@ __device__ long long g_prefill_trace[16];
 constexpr int kStages = 3;
 constexpr float kLazyMaxStep = 8.0f;  // log2 of the growth of a column's maximum that triggers a rescale
 typedef u32x4 __attribute__((address_space(3))) *lds_u4;
-typedef u32x2 __attribute__((address_space(3))) *lds_u2;
 typedef char __attribute__((address_space(3))) *lds_ptr;
 
 template <int D, int BS, int NQ>
@@ -271,15 +270,19 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     constexpr bool MASK = decltype(mask_tag)::value;
     lds_ptr st = (lds_ptr)lds + (tile % kStages) * St::BYTES;
     const int j0 = tile * kTile;
-    // K operand: lane (token r of half T, k-group qg) holds K[token][32c + 8qg .. +7]
+    // The two 16-row score tiles of a 32-token KV tile take interleaved tokens: row m of tile T is
+    // token 8 (m / 4) + 4 T + m % 4.  The accumulator rows a lane holds (4 qg + i of each tile) are then
+    // the eight consecutive tokens 8 qg .. 8 qg + 7, so the V^T operand of the PV product is one
+    // 16-byte LDS read per lane.
+    // K operand: lane (row r of tile T, k-group qg) holds K[token][32c + 8qg .. +7]
     u32x4 kreg[2][NC];
 #pragma unroll
     for (int T = 0; T < 2; ++T) {
-      const int hb = (SB == kTile) ? 0 : T * St::KRUN;
-      const int toff = (SB == kTile) ? 16 * T : 0;
+      const int tok = 8 * (r >> 2) + 4 * T + (r & 3);
+      const int hb = (SB == kTile) ? 0 : (tok / 16) * St::KRUN;
 #pragma unroll
       for (int c = 0; c < NC; ++c)
-        kreg[T][c] = *(lds_u4)(st + hb + ((qg + 4 * c) * SB + toff + r) * 16);
+        kreg[T][c] = *(lds_u4)(st + hb + ((qg + 4 * c) * SB + tok % SB) * 16);
     }
     u32x4 ph[NQ], pl[NQ];
 #pragma unroll
@@ -302,7 +305,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         for (int i = 0; i < 4; ++i) {
           float v = sc[T][i];
           if (MASK) {  // by predicate: unused slots may hold NaN
-            const int j = j0 + 16 * T + 4 * qg + i;
+            const int j = j0 + 8 * qg + 4 * T + i;
             v = j <= p_col[nq] ? v : -INFINITY;
           }
           x[4 * T + i] = v;
@@ -332,16 +335,14 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       split_weights(pv, ph[nq], pl[nq]);
       PTRACE(2 + 2 * nq);  // softmax of this column block
     }
-    // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 4qg..4qg+3 of each half];
-    // V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
-    uint64_t vmask[2] = {~0ull, ~0ull};
+    // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 8qg .. 8qg+7], one 16-byte
+    // piece of the row; V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
+    u32x4 vmask = {~0u, ~0u, ~0u, ~0u};
     if (MASK) {
+      const int keep = min(max(n_kv - j0 - 8 * qg, 0), 8);  // readable tokens among the lane's eight
 #pragma unroll
-      for (int T = 0; T < 2; ++T) {
-        const int nv = n_kv - j0 - 16 * T;
-        const int keep = min(max(nv - 4 * qg, 0), 4);
-        vmask[T] = keep >= 4 ? ~0ull : ((1ull << (16 * keep)) - 1ull);
-      }
+      for (int wd = 0; wd < 4; ++wd)
+        vmask[wd] = keep >= 2 * wd + 2 ? ~0u : (keep == 2 * wd + 1 ? 0xFFFFu : 0u);
     }
     // the denominators: sum over the tile's tokens of the same bf16 pairs, as one more row of V^T
     // that holds ones (every row of the 16 x 16 result is that sum: no cross-lane reduction later)
@@ -350,26 +351,31 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(ph[nq]), lacc[nq], 0, 0, 0);
       lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(pl[nq]), lacc[nq], 0, 0, 0);
     }
+    const int vhalf = (SB == kTile) ? 0 : qg / 2;
+    const int vpiece = (SB == kTile) ? qg : qg % 2;
+    // swizzle(16 c + r) depends on r alone: the piece's position is a lane constant
+    const int vlane = St::KBYTES + vhalf * St::VRUN + r * St::VROW + ((vpiece ^ St::swizzle(r)) * 16);
+    // two row blocks at a time, first all products with the high halves of the weights, then all with
+    // the low halves: an accumulator's two MFMAs are then four MFMAs apart and never wait for each other
 #pragma unroll
-    for (int c = 0; c < ND; ++c) {
-      u32x2 v[2];
+    for (int c = 0; c < ND; c += 2) {
+      bf16x8 va[2];
 #pragma unroll
-      for (int T = 0; T < 2; ++T) {
-        const int hb = St::KBYTES + ((SB == kTile) ? 0 : T * St::VRUN);
-        const int tb = ((SB == kTile ? 16 * T : 0) + 4 * qg) * 2;  // byte of the lane's 4 tokens inside row d
-        // swizzle(16 c + r) depends on r alone: a lane constant
-        v[T] = *(lds_u2)(st + hb + (16 * c + r) * St::VROW + (((tb / 16) ^ St::swizzle(r)) * 16) + tb % 16);
-        if (MASK) {
-          v[T].x &= (uint32_t)vmask[T];
-          v[T].y &= (uint32_t)(vmask[T] >> 32);
-        }
+      for (int u = 0; u < 2; ++u) {
+        u32x4 v = *(lds_u4)(st + vlane + 16 * (c + u) * St::VROW);
+        if (MASK) v &= vmask;
+        va[u] = as_bf16x8(v);
       }
-      const bf16x8 va = as_bf16x8((u32x4){v[0].x, v[0].y, v[1].x, v[1].y});
 #pragma unroll
-      for (int nq = 0; nq < NQ; ++nq) {
-        acc[c][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(ph[nq]), acc[c][nq], 0, 0, 0);
-        acc[c][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, as_bf16x8(pl[nq]), acc[c][nq], 0, 0, 0);
-      }
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+          acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(ph[nq]), acc[c + u][nq], 0, 0, 0);
+#pragma unroll
+      for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+          acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
     }
     PTRACE(5);  // V read + PV
   };
