@@ -203,8 +203,10 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
  *               (identity if it stayed, -1 if it was not live)
  * result        HOST; filled before returning
  * workspace     DEVICE >= pipelive_kv_resize_workspace_bytes(kv), 256-B aligned
- * The call synchronises `stream` once (the feasibility verdict is a host
- * decision) and is complete on the stream order when it returns.
+ * The call waits until the plan (the feasibility verdict) has been computed on
+ * `stream`; the commit is queued behind it and may still be running when the
+ * call returns, ordered on `stream` like any asynchronous call.  A refused
+ * resize modifies nothing.
  */
 typedef struct {
   int64_t n_live, n_moved, old_num_blocks, new_num_blocks;

@@ -109,6 +109,12 @@ int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
     return hip_fail(e);
   }
   memset(kv->pinned, 0, sizeof(HostPinned));
+  e = hipEventCreateWithFlags(&kv->plan_ready, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    (void)hipHostFree(kv->pinned);
+    delete kv;
+    return hip_fail(e);
+  }
   *out = kv;
   return PIPELIVE_OK;
 }
@@ -116,6 +122,7 @@ int32_t pipelive_kv_create(const pipelive_kv_desc_t *d, pipelive_kv_t **out) {
 void pipelive_kv_destroy(pipelive_kv_t *kv) {
   if (!kv) return;
   if (kv->pinned) (void)hipHostFree(kv->pinned);
+  (void)hipEventDestroy(kv->plan_ready);
   delete kv;
 }
 
@@ -318,23 +325,27 @@ int32_t pipelive_kv_resize(pipelive_kv_t *kv, int64_t new_num_blocks, int32_t *c
   HIP_TRY(launch_resize_plan(kv, B, new_num_blocks, plan, move_src, move_dst, st));
   for (int t = 0; t < num_tables; ++t) HIP_TRY(launch_table_check(kv, B, tabs[t], plan, st));
   HIP_TRY(hipMemcpyAsync(kv->pinned->plan, plan, sizeof(ResizePlanOut), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  HIP_TRY(hipEventRecord(kv->plan_ready, st));
+  // The commit is queued behind the plan without waiting for it: its kernels take the verdict from
+  // the plan in device memory and leave everything untouched when it refuses. Only a size beyond
+  // the capacity is a host decision (the device verdict does not know the capacity).
+  const bool fits = new_num_blocks <= kv->d.capacity_blocks;
+  if (fits && new_num_blocks < B)
+    HIP_TRY(launch_resize_commit(kv, B, new_num_blocks, plan, move_src, move_dst, remap, tabs,
+                                 num_tables, st));
+  else if (fits)
+    HIP_TRY(launch_grow(kv, B, new_num_blocks, remap, plan, st));
+  HIP_TRY(hipEventSynchronize(kv->plan_ready));
   const int64_t n_live = kv->pinned->plan[0], n_moved = kv->pinned->plan[1];
   const bool any_dirty = kv->pinned->plan[2] != 0, bad_table = kv->pinned->plan[3] != 0;
   res.n_live = n_live;
-  if (new_num_blocks > kv->d.capacity_blocks) rc = PIPELIVE_E_NOSPACE;
+  if (!fits) rc = PIPELIVE_E_NOSPACE;
   else if (any_dirty) rc = PIPELIVE_E_BUSY;
   else if (n_live > new_num_blocks) rc = PIPELIVE_E_INFEASIBLE;
   else if (bad_table) rc = PIPELIVE_E_RANGE;
 
   if (rc == PIPELIVE_OK) {
-    if (new_num_blocks < B) {
-      HIP_TRY(launch_resize_commit(kv, B, new_num_blocks, n_moved, move_src, move_dst, remap, tabs,
-                                   num_tables, st));
-      res.n_moved = n_moved;
-    } else {
-      HIP_TRY(launch_grow(kv, B, new_num_blocks, remap, st));
-    }
+    if (new_num_blocks < B) res.n_moved = n_moved;
     kv->d.num_blocks = new_num_blocks;
     res.new_num_blocks = new_num_blocks;
   }

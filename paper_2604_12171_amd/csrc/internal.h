@@ -33,6 +33,7 @@ struct pipelive_kv {
   int64_t units_per_block;  // dirty-tracking units per block: 1 or block_tokens
   uint64_t unit_bytes;      // patch bytes of one unit per layer
   pipelive::HostPinned *pinned;
+  hipEvent_t plan_ready;  // recorded after the copy of a resize plan into `pinned`
 };
 
 namespace pipelive {
@@ -102,11 +103,14 @@ hipError_t launch_resize_plan(const pipelive_kv *kv, int64_t B, int64_t B_new, R
                               int32_t *move_src, int32_t *move_dst, hipStream_t st);
 hipError_t launch_table_check(const pipelive_kv *kv, int64_t B, const TableRef &t,
                               ResizePlanOut *plan, hipStream_t st);
-hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new, int64_t n_moved,
-                                const int32_t *move_src, const int32_t *move_dst, int32_t *remap,
-                                const TableRef *tables, int n_tables, hipStream_t st);
+// Both read the verdict (and the number of moves) from `plan` on the device and do nothing when
+// the plan refuses the resize, so they can be queued before the host has seen it.
+hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
+                                const ResizePlanOut *plan, const int32_t *move_src,
+                                const int32_t *move_dst, int32_t *remap, const TableRef *tables,
+                                int n_tables, hipStream_t st);
 hipError_t launch_grow(const pipelive_kv *kv, int64_t B, int64_t B_new, int32_t *remap,
-                       hipStream_t st);
+                       const ResizePlanOut *plan, hipStream_t st);
 
 // ---- patch
 struct LayerList {

@@ -31,6 +31,12 @@ __device__ __forceinline__ u64 range_mask(int64_t word, int64_t lo, int64_t hi) 
   return upto_b & ~upto_a;
 }
 
+// The verdict of the plan, evaluated on the device by every commit kernel: they are queued before the
+// host has seen it (no idle gap on the stream) and do nothing when the resize is refused.
+__device__ __forceinline__ bool plan_ok(const ResizePlanOut *plan, int64_t B_new) {
+  return plan->any_dirty == 0 && plan->bad_table == 0 && plan->n_live <= B_new;
+}
+
 __global__ __launch_bounds__(kScanThreads) void resize_plan_kernel(
     const u64 *live, const u64 *dirty, int64_t n_dirty_units, int64_t B, int64_t B_new,
     ResizePlanOut *plan, int32_t *move_src, int32_t *move_dst) {
@@ -111,11 +117,14 @@ struct MoveArgs {
   int32_t groups;
   uint32_t phys_bytes, sub_bytes, subs_per_block;
   const int32_t *move_src, *move_dst;
-  int64_t n_items;  // n_moved * groups * subs_per_block
+  const ResizePlanOut *plan;  // n_moved and the verdict
+  int64_t B_new;
 };
 
 __global__ __launch_bounds__(kCopyThreads) void move_kernel(MoveArgs a) {
-  for (int64_t item = blockIdx.x; item < a.n_items; item += gridDim.x) {
+  if (!plan_ok(a.plan, a.B_new)) return;
+  const int64_t n_items = a.plan->n_moved * a.groups * a.subs_per_block;
+  for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
     const uint32_t sub = (uint32_t)(item % a.subs_per_block);
     const int64_t e = item / a.subs_per_block;
     const int32_t grp = (int32_t)(e % a.groups);
@@ -132,10 +141,11 @@ __global__ __launch_bounds__(kCopyThreads) void move_kernel(MoveArgs a) {
 // Per-block backing: a move exchanges the two block_list entries of every
 // group instead of copying bytes (the sets of sources and targets are
 // disjoint, so the exchanges are independent).
-__global__ void swap_kernel(uint64_t *block_list, int64_t capacity, int32_t groups, int64_t n_moved,
-                            const int32_t *move_src, const int32_t *move_dst) {
+__global__ void swap_kernel(uint64_t *block_list, int64_t capacity, int32_t groups,
+                            const ResizePlanOut *plan, int64_t B_new, const int32_t *move_src,
+                            const int32_t *move_dst) {
   const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (i >= n_moved * groups) return;
+  if (!plan_ok(plan, B_new) || i >= plan->n_moved * groups) return;
   uint64_t *bl = block_list + (i % groups) * capacity;
   const int64_t k = i / groups;
   const uint64_t a = bl[move_src[k]], b = bl[move_dst[k]];
@@ -145,9 +155,11 @@ __global__ void swap_kernel(uint64_t *block_list, int64_t capacity, int32_t grou
 
 // remap[b] for b in [0,B): identity if live and kept, -1 if not live; moved
 // ids are written from the move list (disjoint from the first set).
-__global__ void remap_kernel(const u64 *live, int64_t B, int64_t B_new, int64_t n_moved,
+__global__ void remap_kernel(const u64 *live, int64_t B, int64_t B_new, const ResizePlanOut *plan,
                              const int32_t *move_src, const int32_t *move_dst, int32_t *remap) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (!plan_ok(plan, B_new)) return;
+  const int64_t n_moved = plan->n_moved;
   if (i < B) {
     const bool lv = (live[i >> 6] >> (i & 63)) & 1ull;
     if (!lv) remap[i] = -1;
@@ -158,7 +170,9 @@ __global__ void remap_kernel(const u64 *live, int64_t B, int64_t B_new, int64_t 
   }
 }
 
-__global__ void table_remap_kernel(TableRef t, const int32_t *remap) {
+__global__ void table_remap_kernel(TableRef t, const int32_t *remap, const ResizePlanOut *plan,
+                                   int64_t B_new) {
+  if (!plan_ok(plan, B_new)) return;
   const int row = blockIdx.x;
   const int used = t.used[row];
   for (int i = threadIdx.x; i < used; i += blockDim.x) {
@@ -167,10 +181,10 @@ __global__ void table_remap_kernel(TableRef t, const int32_t *remap) {
   }
 }
 
-__global__ void live_update_kernel(u64 *live, int64_t n_moved, const int32_t *move_src,
-                                   const int32_t *move_dst) {
+__global__ void live_update_kernel(u64 *live, const ResizePlanOut *plan, int64_t B_new,
+                                   const int32_t *move_src, const int32_t *move_dst) {
   const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (k < n_moved) {
+  if (plan_ok(plan, B_new) && k < plan->n_moved) {
     const int32_t s = move_src[k], d = move_dst[k];
     atomicAnd(&live[s >> 6], ~(1ull << (s & 63)));
     atomicOr(&live[d >> 6], 1ull << (d & 63));
@@ -179,8 +193,9 @@ __global__ void live_update_kernel(u64 *live, int64_t n_moved, const int32_t *mo
 
 // grow: ids [B, B_new) become valid and are neither live nor dirty
 __global__ void grow_kernel(u64 *live, u64 *dirty, int64_t B, int64_t B_new, int64_t upb,
-                            int32_t *remap) {
+                            int32_t *remap, const ResizePlanOut *plan) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (!plan_ok(plan, B_new)) return;
   const int64_t w_lo = B / 64, w_hi = (B_new + 63) / 64;
   if (i < w_hi - w_lo) atomicAnd(&live[w_lo + i], ~range_mask(w_lo + i, B, B_new));
   const int64_t d_lo = B * upb / 64, d_hi = (B_new * upb + 63) / 64;  // dirty units of the new ids
@@ -206,17 +221,21 @@ hipError_t launch_table_check(const pipelive_kv *kv, int64_t B, const TableRef &
   return hipGetLastError();
 }
 
-hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new, int64_t n_moved,
-                                const int32_t *move_src, const int32_t *move_dst, int32_t *remap,
-                                const TableRef *tables, int n_tables, hipStream_t st) {
+hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
+                                const ResizePlanOut *plan, const int32_t *move_src,
+                                const int32_t *move_dst, int32_t *remap, const TableRef *tables,
+                                int n_tables, hipStream_t st) {
+  // grids are sized for the most a shrink can move, B - B_new blocks: the count itself is read from
+  // the plan on the device
   hipError_t e;
-  if (n_moved > 0 && kv->d.block_backing == PIPELIVE_BACKING_PER_BLOCK) {
-    const int64_t n = n_moved * kv->groups;
+  const int64_t max_moved = B - B_new;
+  if (max_moved > 0 && kv->d.block_backing == PIPELIVE_BACKING_PER_BLOCK) {
+    const int64_t n = max_moved * kv->groups;
     hipLaunchKernelGGL(swap_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                        const_cast<uint64_t *>(kv->d.block_list), kv->d.capacity_blocks,
-                       (int32_t)kv->groups, n_moved, move_src, move_dst);
+                       (int32_t)kv->groups, plan, B_new, move_src, move_dst);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-  } else if (n_moved > 0) {
+  } else if (max_moved > 0) {
     MoveArgs a;
     a.block_list = kv->d.block_list;
     a.capacity = kv->d.capacity_blocks;
@@ -226,43 +245,44 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
     a.subs_per_block = (a.phys_bytes + a.sub_bytes - 1) / a.sub_bytes;
     a.move_src = move_src;
     a.move_dst = move_dst;
-    a.n_items = n_moved * kv->groups * a.subs_per_block;
+    a.plan = plan;
+    a.B_new = B_new;
+    const int64_t max_items = max_moved * kv->groups * a.subs_per_block;
     const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();
-    const int grid = (int)(a.n_items < max_grid ? a.n_items : max_grid);
+    const int grid = (int)(max_items < max_grid ? max_items : max_grid);
     hipLaunchKernelGGL(move_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   {
-    const int64_t n = B + n_moved;
+    const int64_t n = B + (max_moved > 0 ? max_moved : 0);
     if (n > 0) {
       hipLaunchKernelGGL(remap_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                         (const u64 *)kv->d.live_bitmap, B, B_new, n_moved, move_src, move_dst,
-                         remap);
+                         (const u64 *)kv->d.live_bitmap, B, B_new, plan, move_src, move_dst, remap);
       if ((e = hipGetLastError()) != hipSuccess) return e;
     }
   }
   for (int t = 0; t < n_tables; ++t) {
     if (tables[t].rows <= 0) continue;
     hipLaunchKernelGGL(table_remap_kernel, dim3(tables[t].rows), dim3(256), 0, st, tables[t],
-                       (const int32_t *)remap);
+                       (const int32_t *)remap, plan, B_new);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  if (n_moved > 0) {
-    hipLaunchKernelGGL(live_update_kernel, dim3((unsigned)((n_moved + 255) / 256)), dim3(256), 0,
-                       st, (u64 *)kv->d.live_bitmap, n_moved, move_src, move_dst);
+  if (max_moved > 0) {
+    hipLaunchKernelGGL(live_update_kernel, dim3((unsigned)((max_moved + 255) / 256)), dim3(256), 0,
+                       st, (u64 *)kv->d.live_bitmap, plan, B_new, move_src, move_dst);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
   return hipSuccess;
 }
 
 hipError_t launch_grow(const pipelive_kv *kv, int64_t B, int64_t B_new, int32_t *remap,
-                       hipStream_t st) {
+                       const ResizePlanOut *plan, hipStream_t st) {
   const int64_t upb = kv->units_per_block;
   const int64_t words = (B_new * upb + 63) / 64 - B * upb / 64 + 1;
   const int64_t n = words > B ? words : B;
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(grow_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                     (u64 *)kv->d.live_bitmap, (u64 *)kv->d.dirty_bitmap, B, B_new, upb, remap);
+                     (u64 *)kv->d.live_bitmap, (u64 *)kv->d.dirty_bitmap, B, B_new, upb, remap, plan);
   return hipGetLastError();
 }
 
