@@ -190,7 +190,8 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
  * block_list entries (of every layer group) are exchanged, so the moved id
  * names the same physical block as before under its new id - the same
  * logical result - and the physical blocks that were free end up at ids >=
- * new_num_blocks, ready to be released.
+ * new_num_blocks, ready to be released once `stream` has been synchronised
+ * (the exchange may still be queued when the call returns).
  * Grow (new_num_blocks > B, <= capacity; the caller has filled the new
  * block_list entries): B becomes new_num_blocks, the new ids are not live, no
  * data moves.
