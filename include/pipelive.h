@@ -160,7 +160,11 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
  * cached tokens 0 .. that position (causal).  q_len = 1 is a decode step.
  *
  * q          DEVICE bf16 [total_q][Hq][D], rows packed sequence after sequence
- * out        DEVICE [total_q][Hq][D], fp32 or bf16, 16-B aligned
+ * out        DEVICE [total_q][Hq][D], fp32 or bf16, 16-B aligned.  The
+ *            precision of the softmax weights in the PV product follows it:
+ *            16 significant bits for fp32 output, one rounded bf16 (the
+ *            output's own precision, a third fewer matrix instructions)
+ *            for bf16 output.
  * q_offsets  DEVICE int32 [num_seqs + 1], q_offsets[0] = 0, non-decreasing
  * total_q    HOST: q_offsets[num_seqs] (sizes the launch)
  * other arguments as for pipelive_paged_attn_decode; no workspace is needed.

@@ -61,7 +61,10 @@ constexpr float kLazyMaxStep = 8.0f;  // log2 of the growth of a column's maximu
 typedef u32x4 __attribute__((address_space(3))) *lds_u4;
 typedef char __attribute__((address_space(3))) *lds_ptr;
 
-template <int D, int BS, int NQ>
+// PAIR: the softmax weights enter the PV product as a pair of bf16 numbers (16 significant bits, for
+// the fp32 output); without it as one rounded bf16, the precision of the bf16 output itself, which
+// saves a third of the matrix instructions and the splitting arithmetic.
+template <int D, int BS, int NQ, bool PAIR>
 __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   using St = Stage<D, BS>;
   constexpr int NC = D / 32, ND = D / 16, SB = St::SB;
@@ -332,7 +335,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         pv[i] = fast_exp2(__builtin_fmaf(x[i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
-      split_weights(pv, ph[nq], pl[nq]);
+      if (PAIR) {
+        split_weights(pv, ph[nq], pl[nq]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) ph[nq][i] = pack_bf16_rne(pv[2 * i], pv[2 * i + 1]);
+      }
       PTRACE(2 + 2 * nq);  // softmax of this column block
     }
     // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 8qg .. 8qg+7], one 16-byte
@@ -349,7 +357,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
       lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(ph[nq]), lacc[nq], 0, 0, 0);
-      lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(pl[nq]), lacc[nq], 0, 0, 0);
+      if (PAIR) lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(pl[nq]), lacc[nq], 0, 0, 0);
     }
     const int vhalf = (SB == kTile) ? 0 : qg / 2;
     const int vpiece = (SB == kTile) ? qg : qg % 2;
@@ -371,11 +379,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq)
           acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(ph[nq]), acc[c + u][nq], 0, 0, 0);
+      if (PAIR) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-          acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
+          for (int nq = 0; nq < NQ; ++nq)
+            acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
+      }
     }
     PTRACE(5);  // V read + PV
   };
@@ -421,7 +431,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     const int ti = col / G, hh = col % G;
     const float inv = lt > 0.f ? 1.0f / lt : 0.f;
     const int64_t row = (int64_t)(q0 + tok0 + ti) * p.Hq + (int64_t)g * G + hh;
-    if (p.out_dtype == PIPELIVE_OUT_F32) {
+    if (PAIR) {  // fp32 output
       float *dst = (float *)p.out + row * D + 4 * qg;
 #pragma unroll
       for (int c = 0; c < ND; ++c)
@@ -441,7 +451,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 
 template <int D, int BS>
 hipError_t launch_t(const PrefillParams &p, hipStream_t st) {
-  hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
+  if (p.out_dtype == PIPELIVE_OUT_F32)
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, true>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
+  else
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, false>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
   return hipGetLastError();
 }
 

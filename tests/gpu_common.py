@@ -79,3 +79,10 @@ def attn_errors(got: np.ndarray, ref: np.ndarray):
 
 
 MAX_ABS, REL_L2 = 1e-2, 2e-3  # tolerance of the attention output (bf16 in, fp32 accumulate)
+
+# Prefill attention with bf16 output: the output is rounded to bf16 (relative error <= 2^-9 per element)
+# and the kernel then also rounds each softmax weight p_j to one bf16 before the PV product (<= 2^-9
+# relative per weight, in numerator and denominator).  Per element |err| <= 2^-9 (2 |o| + max|v|): with
+# the generator's |v| <= 4.4 and |o| <= max|v| that is < 2.6e-2; in the L2 norm the output rounding alone
+# is <= 2^-9 = 1.95e-3 and the independent weight roundings add about 2^-9 / sqrt(3).
+BF16_MAX_ABS, BF16_REL_L2 = 3e-2, 4e-3

@@ -23,7 +23,7 @@ import oracle
 import pipelive_inputs as pin
 from pipelive_inputs.device_fill import fill_live_blocks
 import paper_2604_12171_amd as P
-from gpu_common import MAX_ABS, REL_L2, attn_errors, bitmap_ids
+from gpu_common import BF16_MAX_ABS, BF16_REL_L2, MAX_ABS, REL_L2, attn_errors, bitmap_ids
 
 pytestmark = pytest.mark.gpu
 SEED = pin.MASTER_SEED
@@ -385,7 +385,14 @@ def test_prefill_chunk_in_bench_configuration():
     torch.cuda.synchronize()
     got = out.cpu().numpy()
     assert np.isfinite(got).all()
+    out16 = torch.full((tq, cfg.num_q_heads, cfg.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda")
+    P.pipelive_paged_attn_prefill(region, 0, q_d, out16, torch.from_numpy(batch.table).cuda(),
+                                  torch.from_numpy(batch.ctx_lens).cuda(), qo, tq)
+    torch.cuda.synchronize()
+    got16 = out16.float().cpu().numpy()
+    assert np.isfinite(got16).all()
     worst = (0.0, 0.0)
+    worst16 = (0.0, 0.0)
     for s in (0, 5, 11, 15):
         u = int(batch.used[s])
         host = oracle.HostKV(1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, u,
@@ -399,7 +406,11 @@ def test_prefill_chunk_in_bench_configuration():
             ma, rl = attn_errors(got[s * q_len + i], ref)
             assert ma <= MAX_ABS and rl <= REL_L2, (s, i, ma, rl)
             worst = (max(worst[0], ma), max(worst[1], rl))
-    log(f"  prefill: 32 sampled rows, worst max_abs {worst[0]:.2e} rel_l2 {worst[1]:.2e}")
+            ma, rl = attn_errors(got16[s * q_len + i], ref)
+            assert ma <= BF16_MAX_ABS and rl <= BF16_REL_L2, ("bf16 out", s, i, ma, rl)
+            worst16 = (max(worst16[0], ma), max(worst16[1], rl))
+    log(f"  prefill: 32 sampled rows, worst max_abs {worst[0]:.2e} rel_l2 {worst[1]:.2e}; "
+        f"bf16 output: {worst16[0]:.2e} {worst16[1]:.2e}")
     assert P.pipelive_kv_read_state(region).status == 0
     del region
     torch.cuda.empty_cache()
