@@ -1,5 +1,5 @@
 // Host side of the C ABI: argument validation, launch heuristics, and the one
-// synchronisation that ResizeKV needs for its feasibility verdict.
+// wait (on the plan, not on the commit) that ResizeKV needs to return its verdict.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>

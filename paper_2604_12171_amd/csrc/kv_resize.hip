@@ -6,10 +6,11 @@
 //           free ids in the head [0, B_new) (prefix sums of popcounts), and
 //           whether any dirty bit is pending.  It changes nothing.
 // check   : every used table entry must be a live id below B.
-// commit  : (after the host has read the verdict) copy block T[k] -> F[k] in
-//           every layer group, build remap[], rewrite the tables, move the
-//           live bits.  Sources and destinations are disjoint id sets, so the
-//           copy needs no ordering.
+// commit  : copy block T[k] -> F[k] in every layer group, build remap[],
+//           rewrite the tables, move the live bits.  Sources and destinations
+//           are disjoint id sets, so the copy needs no ordering.  The commit
+//           kernels are queued right behind the plan and read its verdict on
+//           the device: a refused resize changes nothing.
 #include "internal.h"
 #include "kv_copy.h"
 #include "scan.h"
