@@ -97,6 +97,63 @@ def test_prefill_single_query_agrees_with_decode_kernel_and_bf16_out():
     assert ma <= BF16_MAX_ABS and rl <= BF16_REL_L2, (ma, rl)
 
 
+def test_prefill_many_sequences_multi_chunk_unit_search():
+    """More than 64 sequences (the unit search scans them 64 at a time), among them sequences without
+    queries and one-token chunks."""
+    rng = np.random.default_rng(5)
+    S = 150
+    ctx = rng.integers(1, 90, size=S)
+    qlen = np.minimum(ctx, rng.integers(0, 40, size=S))
+    qlen[::7] = 0
+    qlen[3::11] = 1
+    cfg = pin.StageConfig("pf", 1, 4, 2, 64, 16, S, 0, 0)
+    batch = _batch(cfg, ctx)
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
+    total_q = int(qo[-1])
+    q = pin.f32_to_bf16_bits(rng.standard_normal((total_q, 4, 64)).astype(np.float32))
+    q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    out = torch.full((total_q, 4, 64), float("nan"), dtype=torch.float32, device="cuda")
+    P.pipelive_paged_attn_prefill(dev, 0, q_d, out, torch.from_numpy(batch.table).cuda(),
+                                  torch.from_numpy(batch.ctx_lens).cuda(), torch.from_numpy(qo).cuda(), total_q)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = host.attn_prefill(0, q, batch.table, batch.ctx_lens, qo, nthreads=8)
+    assert np.isfinite(got).all()
+    for s in range(S):
+        if qlen[s]:
+            ma, rl = attn_errors(got[qo[s]:qo[s + 1]], ref[qo[s]:qo[s + 1]])
+            assert ma <= MAX_ABS and rl <= REL_L2, (s, ma, rl)
+    assert P.pipelive_kv_read_state(dev).status == 0
+
+
+def test_prefill_bad_table_entry_sets_status_and_spares_the_others():
+    ctx, qlen = [100, 64, 200], [100, 10, 50]
+    cfg = pin.StageConfig("pf", 1, 8, 2, 128, 16, 3, 0, 0)
+    batch = _batch(cfg, ctx)
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
+    total_q = int(qo[-1])
+    rng = np.random.default_rng(8)
+    q = pin.f32_to_bf16_bits(rng.standard_normal((total_q, 8, 128)).astype(np.float32))
+    q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    table = batch.table.copy()
+    table[1, 2] = 10 ** 6        # beyond the pool
+    table[1, 0] = -3             # negative
+    out = torch.full((total_q, 8, 128), float("nan"), dtype=torch.float32, device="cuda")
+    P.pipelive_paged_attn_prefill(dev, 0, q_d, out, torch.from_numpy(table).cuda(),
+                                  torch.from_numpy(batch.ctx_lens).cuda(), torch.from_numpy(qo).cuda(), total_q)
+    torch.cuda.synchronize()
+    assert P.pipelive_kv_read_state(dev).status == P.E_RANGE
+    got = out.cpu().numpy()
+    ref = host.attn_prefill(0, q, batch.table, batch.ctx_lens, qo, nthreads=8)
+    for s in (0, 2):             # the sequences with valid tables are unaffected
+        ma, rl = attn_errors(got[qo[s]:qo[s + 1]], ref[qo[s]:qo[s + 1]])
+        assert ma <= MAX_ABS and rl <= REL_L2, (s, ma, rl)
+
+
 def test_prefill_errors():
     cfg = pin.StageConfig("pf", 1, 4, 2, 64, 16, 1, 0, 0)
     batch = _batch(cfg, [10])
