@@ -287,42 +287,65 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       for (int c = 0; c < NC; ++c)
         kreg[T][c] = *(lds_u4)(st + hb + ((qg + 4 * c) * SB + tok % SB) * 16);
     }
-    u32x4 ph[NQ], pl[NQ];
+    // QK^T: the 2 NQ score tiles are independent accumulator chains, issued round-robin so that a
+    // chain's next product never waits for its previous one
+    f32x4 sc[NQ][2];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+      for (int T = 0; T < 2; ++T) sc[nq][T] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+          sc[nq][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[T][c]), qreg[nq][c], sc[nq][T], 0, 0, 0);
+    // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 8qg .. 8qg+7], one 16-byte
+    // piece of the row.  All row blocks are requested here, behind the QK products, so that they
+    // arrive while the softmax runs and the PV products can be issued back to back.
+    const int vhalf = (SB == kTile) ? 0 : qg / 2;
+    const int vpiece = (SB == kTile) ? qg : qg % 2;
+    // swizzle(16 c + r) depends on r alone: the piece's position is a lane constant
+    const int vlane = St::KBYTES + vhalf * St::VRUN + r * St::VROW + ((vpiece ^ St::swizzle(r)) * 16);
+    u32x4 vreg[ND];
+#pragma unroll
+    for (int c = 0; c < ND; ++c) vreg[c] = *(lds_u4)(st + vlane + 16 * c * St::VROW);
+    __builtin_amdgcn_sched_barrier(0);
+    PTRACE(1);  // K read, QK, V requests
+
+    // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
+    float x[NQ][8];
+    float m_seen[NQ];
+    bool grow = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      f32x4 sc[2];
-#pragma unroll
-      for (int T = 0; T < 2; ++T) {
-        sc[T] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < NC; ++c)
-          sc[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kreg[T][c]), qreg[nq][c], sc[T], 0, 0, 0);
-      }
-      PTRACE(1 + 2 * nq);  // K read + QK of this column block
-      // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
-      float x[8];
       float mloc = -INFINITY;
 #pragma unroll
       for (int T = 0; T < 2; ++T)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float v = sc[T][i];
+          float v = sc[nq][T][i];
           if (MASK) {  // by predicate: unused slots may hold NaN
             const int j = j0 + 8 * qg + 4 * T + i;
             v = j <= p_col[nq] ? v : -INFINITY;
           }
-          x[4 * T + i] = v;
+          x[nq][4 * T + i] = v;
           mloc = fmaxf(mloc, v);
         }
       mloc = xor16_max(mloc);
       mloc = xor32_max(mloc);
-      // m is kept in the scaled domain and only follows the running maximum when that has grown by
-      // more than 2^8: until then the weights are taken against the older reference (they stay below
-      // 2^8, harmless in fp32 sums and in the bf16 pair) and the accumulators need no rescaling.  The
-      // common factor cancels in O / l, so the result is the same softmax.
-      const float m_seen = fmaxf(m[nq], mloc * p.scale_log2);
-      if (__any(m_seen - m[nq] > kLazyMaxStep)) {  // rare after the first tiles; -inf -> finite counts as growth
-        const float m_new = (m_seen - m[nq] > kLazyMaxStep) ? m_seen : m[nq];
+      m_seen[nq] = fmaxf(m[nq], mloc * p.scale_log2);
+      grow |= m_seen[nq] - m[nq] > kLazyMaxStep;
+    }
+    // m is kept in the scaled domain and only follows the running maximum when that has grown by
+    // more than 2^8: until then the weights are taken against the older reference (they stay below
+    // 2^8, harmless in fp32 sums and in the bf16 pair) and the accumulators need no rescaling.  The
+    // common factor cancels in O / l, so the result is the same softmax.
+    if (__any(grow)) {  // rare after the first tiles; -inf -> finite counts as growth
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) {
+        const float m_new = (m_seen[nq] - m[nq] > kLazyMaxStep) ? m_seen[nq] : m[nq];
         // a column that has seen nothing yet (m_new still -inf, masked tiles only) keeps its state
         const float alpha = (m_new == -INFINITY) ? 1.0f : fast_exp2(m[nq] - m_new);
         m[nq] = m_new;
@@ -330,61 +353,55 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
         for (int c = 0; c < ND; ++c) acc[c][nq] *= alpha;
       }
+    }
+    u32x4 ph[NQ], pl[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
       const float neg_m = (MASK && m[nq] == -INFINITY) ? 0.f : -m[nq];
       float pv[8];
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        pv[i] = fast_exp2(__builtin_fmaf(x[i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
+        pv[i] = fast_exp2(__builtin_fmaf(x[nq][i], p.scale_log2, neg_m));  // exp2(-inf) = 0 for masked scores
       if (PAIR) {
         split_weights(pv, ph[nq], pl[nq]);
       } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) ph[nq][i] = pack_bf16_rne(pv[2 * i], pv[2 * i + 1]);
       }
-      PTRACE(2 + 2 * nq);  // softmax of this column block
     }
-    // V^T operand: lane (row d = 16c + r, k-group qg) holds V[d][tokens 8qg .. 8qg+7], one 16-byte
-    // piece of the row; V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
-    u32x4 vmask = {~0u, ~0u, ~0u, ~0u};
+    PTRACE(2);  // softmax
+    // V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
     if (MASK) {
+      u32x4 vmask;
       const int keep = min(max(n_kv - j0 - 8 * qg, 0), 8);  // readable tokens among the lane's eight
 #pragma unroll
       for (int wd = 0; wd < 4; ++wd)
         vmask[wd] = keep >= 2 * wd + 2 ? ~0u : (keep == 2 * wd + 1 ? 0xFFFFu : 0u);
+#pragma unroll
+      for (int c = 0; c < ND; ++c) vreg[c] &= vmask;
     }
-    // the denominators: sum over the tile's tokens of the same bf16 pairs, as one more row of V^T
+    // the denominators: sum over the tile's tokens of the same bf16 weights, as one more row of V^T
     // that holds ones (every row of the 16 x 16 result is that sum: no cross-lane reduction later)
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
       lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(ph[nq]), lacc[nq], 0, 0, 0);
       if (PAIR) lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(pl[nq]), lacc[nq], 0, 0, 0);
     }
-    const int vhalf = (SB == kTile) ? 0 : qg / 2;
-    const int vpiece = (SB == kTile) ? qg : qg % 2;
-    // swizzle(16 c + r) depends on r alone: the piece's position is a lane constant
-    const int vlane = St::KBYTES + vhalf * St::VRUN + r * St::VROW + ((vpiece ^ St::swizzle(r)) * 16);
     // two row blocks at a time, first all products with the high halves of the weights, then all with
     // the low halves: an accumulator's two MFMAs are then four MFMAs apart and never wait for each other
 #pragma unroll
     for (int c = 0; c < ND; c += 2) {
-      bf16x8 va[2];
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        u32x4 v = *(lds_u4)(st + vlane + 16 * (c + u) * St::VROW);
-        if (MASK) v &= vmask;
-        va[u] = as_bf16x8(v);
-      }
 #pragma unroll
       for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq)
-          acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(ph[nq]), acc[c + u][nq], 0, 0, 0);
+          acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vreg[c + u]), as_bf16x8(ph[nq]), acc[c + u][nq], 0, 0, 0);
       if (PAIR) {
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
           for (int nq = 0; nq < NQ; ++nq)
-            acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[u], as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
+            acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vreg[c + u]), as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
       }
     }
     PTRACE(5);  // V read + PV
