@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     uint64_t a0, a1;
     bool bad;
     tile_addr(t, a0, a1, bad);
-    if (bad) return;  // the batch is skipped by every wave: whatever the stage holds is never used
+    if (__builtin_expect(bad, 0)) return;  // the batch is skipped by every wave: whatever the stage holds is never used
     lds_ptr st = (lds_ptr)lds + (t % kStages) * St::BYTES + w * 1024;
 #pragma unroll
     for (int j = 0; j < St::PER_THREAD; ++j) {
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   // in flight (a plain __syncthreads() would wait for them too and halve the prefetch distance).
   auto tile_barrier = [&](bool newest_tile_in_flight) {
     asm volatile("" ::: "memory");
-    if (newest_tile_in_flight) {
+    if (__builtin_expect(newest_tile_in_flight, 1)) {
       if (St::PER_THREAD == 4) __builtin_amdgcn_s_waitcnt(0x0074);  // vmcnt(4) lgkmcnt(0)
       else __builtin_amdgcn_s_waitcnt(0x0072);                      // vmcnt(2) lgkmcnt(0)
     } else {
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     // more than 2^8: until then the weights are taken against the older reference (they stay below
     // 2^8, harmless in fp32 sums and in the bf16 pair) and the accumulators need no rescaling.  The
     // common factor cancels in O / l, so the result is the same softmax.
-    if (__any(grow)) {  // rare after the first tiles; -inf -> finite counts as growth
+    if (__builtin_expect(__any(grow), 0)) {  // rare after the first tiles; -inf -> finite counts as growth
 #pragma unroll
       for (int nq = 0; nq < NQ; ++nq) {
         const float m_new = (m_seen[nq] - m[nq] > kLazyMaxStep) ? m_seen[nq] : m[nq];
@@ -418,13 +418,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   auto step = [&](int t, auto mask_tag) {
     PTRACE_START();
     const bool more = t + 2 < nt_wg;
-    if (more) stage_load(t + 2);
+    if (__builtin_expect(more, 1)) stage_load(t + 2);
     const int batch = t / kSubTiles;
     const bool bad = (bad_bits >> (batch & 1)) & 1u;
     // a quarter into a batch the slot of the batch before it is free: resolve the batch after it
-    if (t % kSubTiles == 8 && batch >= 1) resolve_into_slot(batch + 1);
+    if (__builtin_expect(t % kSubTiles == 8 && batch >= 1, 0)) resolve_into_slot(batch + 1);
     PTRACE(0);  // issue of the copies
-    if (t < nt_w && !bad) compute(t, mask_tag);
+    if (__builtin_expect(t < nt_w && !bad, 1)) compute(t, mask_tag);
     PTRACE(6);
     tile_barrier(more);  // tile t+1 must be in LDS past the barrier; the copies of tile t+2 may still fly
     PTRACE(7);           // wait for the copies + barrier
