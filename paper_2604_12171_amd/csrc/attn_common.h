@@ -32,6 +32,27 @@ __device__ __forceinline__ float xor32_max(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// max(a, b) for values that are never NaN, as the bare instruction: fmaxf() would first quiet each
+// operand that the compiler cannot prove canonical (one more instruction per operand).
+__device__ __forceinline__ float max_no_nan(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+// The maximum over the four 16-lane rows of a and of b, per lane position inside the row, for both
+// values at once: the first swap pairs the rows of a and b (rows 0, 2 then hold a's pair maxima, rows
+// 1, 3 b's), the second joins the two halves, the third hands every row both results.  Three swaps
+// and two maxima instead of four and four.  Inputs must not be NaN.
+__device__ __forceinline__ void rows_max_pair(float a, float b, float &ma, float &mb) {
+  const auto r1 = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+  const float y = max_no_nan(__uint_as_float(r1[0]), __uint_as_float(r1[1]));
+  const auto r2 = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  const float z = max_no_nan(__uint_as_float(r2[0]), __uint_as_float(r2[1]));
+  const auto r3 = __builtin_amdgcn_permlane16_swap(__float_as_uint(z), __float_as_uint(z), false, false);
+  ma = __uint_as_float(r3[0]);
+  mb = __uint_as_float(r3[1]);
+}
+
 // two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32 on gfx950)
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));

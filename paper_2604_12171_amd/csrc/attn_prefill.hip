@@ -148,7 +148,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   f32x4 acc[ND][NQ];
   f32x4 lacc[NQ];  // every element: the column's running denominator
   float m[NQ];
-  const bf16x8 ones = as_bf16x8((u32x4){0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
+  // kept opaque so that it stays in registers instead of being rebuilt from scalars in every tile
+  u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  asm volatile("" : "+v"(ones_bits));
+  const bf16x8 ones = as_bf16x8(ones_bits);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     m[nq] = -INFINITY;
@@ -193,12 +196,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     // use the address here, so that the wait for its load is placed here (once per 32 tiles) and not
     // in front of every later read of it, where it would also wait for the tile copies in flight
     asm volatile("" : "+v"(rv.addr));
+    // the flags are wave-uniform: kept in a scalar register, their tests cost no vector instruction
     if (batch & 1) {
       addr_b = rv.addr;
-      bad_bits = (bad_bits & 1u) | (rv.bad << 1);
+      bad_bits = __builtin_amdgcn_readfirstlane((bad_bits & 1u) | (rv.bad << 1));
     } else {
       addr_a = rv.addr;
-      bad_bits = (bad_bits & 2u) | rv.bad;
+      bad_bits = __builtin_amdgcn_readfirstlane((bad_bits & 2u) | rv.bad);
     }
   };
   // addresses of the two runs' sub-blocks of tile t (the same sub-block twice when SB = 32)
@@ -316,11 +320,11 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 
     // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
     float x[NQ][8];
-    float m_seen[NQ];
+    float m_seen[NQ], mloc[NQ];
     bool grow = false;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
-      float mloc = -INFINITY;
+      mloc[nq] = -INFINITY;
 #pragma unroll
       for (int T = 0; T < 2; ++T)
 #pragma unroll
@@ -331,11 +335,19 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
             v = j <= p_col[nq] ? v : -INFINITY;
           }
           x[nq][4 * T + i] = v;
-          mloc = fmaxf(mloc, v);
+          mloc[nq] = fmaxf(mloc[nq], v);
         }
-      mloc = xor16_max(mloc);
-      mloc = xor32_max(mloc);
-      m_seen[nq] = fmaxf(m[nq], mloc * p.scale_log2);
+    }
+    // column maxima across the four 16-lane rows (the scores that reach here are never NaN)
+    if (NQ == 2) {
+      rows_max_pair(mloc[0], mloc[1], mloc[0], mloc[1]);
+    } else {
+#pragma unroll
+      for (int nq = 0; nq < NQ; ++nq) mloc[nq] = xor32_max(xor16_max(mloc[nq]));
+    }
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+      m_seen[nq] = max_no_nan(m[nq], mloc[nq] * p.scale_log2);
       grow |= m_seen[nq] - m[nq] > kLazyMaxStep;
     }
     // m is kept in the scaled domain and only follows the running maximum when that has grown by
