@@ -81,14 +81,20 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   const int unit = blockIdx.x;
 
   // ---- locate the unit: units of sequence s = Hkv * ceil(q_len / WB), ordered (s, head, block)
-  int s = -1, nwb = 0;
+  // (the lanes that scan the sequences also fetch what the unit needs of its sequence, so that no
+  // second round trip to memory follows the search)
+  int s = -1, nwb = 0, q0 = 0, qlen = 0, n = 0;
   int64_t rem = 0;
   {
     int64_t carry = 0;
     for (int base = 0; base < S && s < 0; base += 64) {
       const bool in = base + lane < S;
-      int ql = 0;
-      if (in) ql = p.q_offsets[base + lane + 1] - p.q_offsets[base + lane];
+      int qa = 0, ql = 0, cx = 0;
+      if (in) {
+        qa = p.q_offsets[base + lane];
+        ql = p.q_offsets[base + lane + 1] - qa;
+        cx = p.ctx[base + lane];
+      }
       const int nb = ql > 0 ? (ql + WB - 1) / WB : 0;
       const int units = nb * Hkv;
       const int inc = wave_inclusive_scan(units, lane);
@@ -97,6 +103,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         const int k = __ffsll((long long)bal) - 1;
         s = base + k;
         nwb = __builtin_amdgcn_readlane(nb, k);
+        q0 = __builtin_amdgcn_readlane(qa, k);
+        qlen = __builtin_amdgcn_readlane(ql, k);
+        n = __builtin_amdgcn_readlane(cx, k);
         rem = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
       }
       carry += __builtin_amdgcn_readlane(inc, 63);
@@ -105,8 +114,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   if (s < 0) return;  // beyond the last unit (whole workgroup: the decision is the same in every wave)
   // later query blocks attend to more tokens: hand them out first so the launch ends evenly
   const int g = (int)(rem / nwb), wb = nwb - 1 - (int)(rem % nwb);
-  const int q0 = p.q_offsets[s], qlen = p.q_offsets[s + 1] - q0;
-  int n = p.ctx[s];
   if (n > p.max_ctx) n = p.max_ctx;
   if (qlen > n) {  // more queries than cached tokens: flag and skip
     if (tid == 0) atomicCAS(p.status, 0, PIPELIVE_E_INVAL);
