@@ -42,20 +42,6 @@ struct Stage {
   static constexpr int PER_THREAD = CHUNKS / 256;       // 4 (D 128) or 2 (D 64)
 };
 
-#ifdef PIPELIVE_PREFILL_TRACE
-// development builds: shader-clock totals per phase, summed over the tiles of wave 0 of workgroup 0
-__device__ long long g_prefill_trace[16];
-#define PTRACE_DECL long long tr_t0 = 0; long long tr_acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}; const bool tr_on = blockIdx.x == 0 && tid < 64; const long long tr_c0 = clock64(), tr_w0 = wall_clock64()
-#define PTRACE_START() do { __builtin_amdgcn_sched_barrier(0); tr_t0 = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
-#define PTRACE(k) do { __builtin_amdgcn_sched_barrier(0); const long long n_ = clock64(); tr_acc[k] += n_ - tr_t0; tr_t0 = n_; __builtin_amdgcn_sched_barrier(0); } while (0)
-#define PTRACE_FLUSH(ntiles) do { if (tr_on && lane == 0) { for (int i_ = 0; i_ < 8; ++i_) g_prefill_trace[i_] = tr_acc[i_]; g_prefill_trace[8] = (ntiles); g_prefill_trace[9] = clock64() - tr_c0; g_prefill_trace[10] = wall_clock64() - tr_w0; } } while (0)
-#else
-#define PTRACE_DECL do {} while (0)
-#define PTRACE_START() do {} while (0)
-#define PTRACE(k) do {} while (0)
-#define PTRACE_FLUSH(n) do {} while (0)
-#endif
-
 constexpr int kStages = 3;
 constexpr float kLazyMaxStep = 8.0f;  // log2 of the growth of a column's maximum that triggers a rescale
 typedef u32x4 __attribute__((address_space(3))) *lds_u4;
@@ -71,54 +57,235 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   __shared__ __attribute__((aligned(16))) char lds[kStages * St::BYTES];
 
   const int tid = threadIdx.x;
-  PTRACE_DECL;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r = lane & 15, qg = lane >> 4;
   const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
   const int QB = (NQ * 16) / G;  // query tokens per wave
   const int WB = 4 * QB;         // query tokens per workgroup
-  const int unit = blockIdx.x;
+  const int grid = gridDim.x;
+  __shared__ int mailbox;  // the ticket that thread 0 drew, for the other waves
 
-  // ---- locate the unit: units of sequence s = Hkv * ceil(q_len / WB), ordered (s, head, block)
-  // (the lanes that scan the sequences also fetch what the unit needs of its sequence, so that no
-  // second round trip to memory follows the search)
-  int s = -1, nwb = 0, q0 = 0, qlen = 0, n = 0;
-  int64_t rem = 0;
-  {
+  // ---- work units: units of sequence s = Hkv * ceil(q_len / WB), ordered (s, head, block); the later
+  // query blocks of a sequence attend to more tokens and come first.  The lanes that scan the
+  // sequences also fetch what the unit needs of its sequence (no second round trip after the search).
+  struct Unit {
+    int s, g, wb, q0, qlen, n;  // s < 0: no such unit
+  };
+  struct Scan {
+    int qa, ql, cx;  // q_offsets[i], q_len and context length of sequence base + lane
+  };
+  auto scan_issue = [&](int base) -> Scan {
+    Scan sc = {0, 0, 0};
+    if (base + lane < S) {
+      sc.qa = p.q_offsets[base + lane];
+      sc.ql = p.q_offsets[base + lane + 1] - sc.qa;
+      sc.cx = p.ctx[base + lane];
+    }
+    return sc;
+  };
+  auto locate = [&](int unit, Scan first) -> Unit {
+    Unit u = {-1, 0, 0, 0, 0, 0};
     int64_t carry = 0;
-    for (int base = 0; base < S && s < 0; base += 64) {
-      const bool in = base + lane < S;
-      int qa = 0, ql = 0, cx = 0;
-      if (in) {
-        qa = p.q_offsets[base + lane];
-        ql = p.q_offsets[base + lane + 1] - qa;
-        cx = p.ctx[base + lane];
-      }
-      const int nb = ql > 0 ? (ql + WB - 1) / WB : 0;
+    for (int base = 0; base < S && u.s < 0; base += 64) {
+      const Scan sc = base == 0 ? first : scan_issue(base);
+      const int nb = sc.ql > 0 ? (sc.ql + WB - 1) / WB : 0;
       const int units = nb * Hkv;
       const int inc = wave_inclusive_scan(units, lane);
-      const uint64_t bal = __ballot(in && carry + inc > unit);  // first sequence whose range holds it
+      const uint64_t bal = __ballot(carry + inc > unit);  // first sequence whose range holds it
       if (bal) {
         const int k = __ffsll((long long)bal) - 1;
-        s = base + k;
-        nwb = __builtin_amdgcn_readlane(nb, k);
-        q0 = __builtin_amdgcn_readlane(qa, k);
-        qlen = __builtin_amdgcn_readlane(ql, k);
-        n = __builtin_amdgcn_readlane(cx, k);
-        rem = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
+        const int nwb = __builtin_amdgcn_readlane(nb, k);
+        const int64_t rem = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
+        u.s = base + k;
+        u.g = (int)(rem / nwb);
+        u.wb = nwb - 1 - (int)(rem % nwb);
+        u.q0 = __builtin_amdgcn_readlane(sc.qa, k);
+        u.qlen = __builtin_amdgcn_readlane(sc.ql, k);
+        u.n = min(__builtin_amdgcn_readlane(sc.cx, k), p.max_ctx);
       }
       carry += __builtin_amdgcn_readlane(inc, 63);
     }
+    return u;
+  };
+  // tiles and blocks that the workgroup of a unit walks
+  auto unit_tiles = [&](const Unit &u) { return (u.n - u.qlen + min((u.wb + 1) * WB, u.qlen) - 1 + kTile) / kTile; };
+  auto unit_blocks = [&](const Unit &u) { return (u.n - u.qlen + min((u.wb + 1) * WB, u.qlen) + BS - 1) / BS; };
+
+  // ---- block addresses of a unit's first 32 tiles (one block per lane), in two dependent loads
+  constexpr int TPB = BS >= kTile ? BS / kTile : 1;  // tiles per block (a 16-token block is half a tile)
+  auto batch_blocks = [&](int batch, int nt, int nblocks) {  // blocks of the batch that exist: [first, first + count)
+    const int t_lo = batch * kSubTiles, t_hi = min(t_lo + kSubTiles, nt);
+    const int first = BS < kTile ? t_lo * 2 : t_lo / TPB;
+    const int last = BS < kTile ? t_hi * 2 - 1 : (t_hi - 1) / TPB;
+    return min(last + 1, nblocks) - first;
+  };
+  auto table_issue = [&](const Unit &u) -> int {  // block id of this lane's block in batch 0, -1: none
+    const int nblk = batch_blocks(0, unit_tiles(u), unit_blocks(u));
+    return lane < nblk ? p.table[(int64_t)u.s * p.table_stride + lane] : -1;
+  };
+  auto list_issue = [&](const Unit &u, int id, uint32_t &bad) -> uint64_t {
+    const int nblk = batch_blocks(0, unit_tiles(u), unit_blocks(u));
+    const bool have = lane < nblk;
+    const bool ok = have && (uint32_t)id < (uint64_t)p.num_blocks;
+    const bool lane_bad = have && !ok;
+    bad = __any(lane_bad) ? 1u : 0u;  // never dereference a bad id: flag it and leave the batch's tokens out
+    if (lane_bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);
+    return ok ? p.block_list[id] : 0;
+  };
+
+  // ---- the next unit is drawn, searched and resolved one step per tile of the current unit, so
+  // that its memory round trips (ticket, sequence scan, table, block list) hide behind arithmetic.
+  // The steps' loads are LDS-direct loads into a few rows of LDS per wave: nothing is pending in a
+  // vector register while the tile loop runs (the compiler guards every reuse of a register with a
+  // pending load by a wait for ALL memory operations, the tile copies in flight included).  They are
+  // older than the tile copies issued after them, so the wait of the tile's barrier covers them and
+  // the next iteration reads the rows.  Only the ticket comes back in a register; thread 0 passes it
+  // on at the end of the same iteration.  Every wave runs the same steps; `cs` is uniform over the
+  // workgroup.
+  constexpr int kChainReady = 5, kChainEnd = 6;
+  constexpr int kRows = 6;  // q_offsets[i], q_offsets[i + 1], ctx[i], table entry, block list entry (two halves)
+  __shared__ uint32_t chain_rows[4 * kRows * 64];
+  typedef uint32_t __attribute__((address_space(3))) *lds_u1;
+  typedef const uint32_t __attribute__((address_space(1))) *global_u1;
+  auto row = [&](int k) { return chain_rows + (w * kRows + k) * 64; };
+  auto row_fetch = [&](int k, const void *lane_src) {  // lane i: 4 bytes from its address -> row k, word i
+    __builtin_amdgcn_global_load_lds((global_u1)lane_src, (lds_u1)row(k), 4, 0, 0);
+  };
+  int cs = kChainEnd;
+  int c_ticket = 0;  // thread 0: the ticket it drew
+  int c_unit = -1;
+  Unit nxt = {-1, 0, 0, 0, 0, 0};
+  uint64_t nxt_addr = 0;
+  uint32_t nxt_bad = 0;
+  // what is uniform goes through readfirstlane, so that it provably lives in scalar registers
+  auto uniform_unit = [&](const Unit &u) -> Unit {
+    Unit o;
+    o.s = __builtin_amdgcn_readfirstlane(u.s);
+    o.g = __builtin_amdgcn_readfirstlane(u.g);
+    o.wb = __builtin_amdgcn_readfirstlane(u.wb);
+    o.q0 = __builtin_amdgcn_readfirstlane(u.q0);
+    o.qlen = __builtin_amdgcn_readfirstlane(u.qlen);
+    o.n = __builtin_amdgcn_readfirstlane(u.n);
+    return o;
+  };
+  // Before the tile's arithmetic: take up what the step before fetched, fetch for the next one.
+  auto chain_step = [&]() {
+    int next_cs = cs;
+    switch (cs) {
+      case 0:  // draw a ticket
+        if (tid == 0) c_ticket = atomicAdd(p.ticket, 1);
+        break;  // chain_pass_on() moves on
+      case 1:  // the ticket is in the mailbox: fetch the first 64 sequences' offsets and lengths
+        c_unit = grid + __builtin_amdgcn_readfirstlane(mailbox);
+        if (c_unit >= p.num_units) {
+          next_cs = kChainEnd;
+        } else {
+          if (lane < S) {
+            row_fetch(0, p.q_offsets + lane);
+            row_fetch(1, p.q_offsets + lane + 1);
+            row_fetch(2, p.ctx + lane);
+          }
+          next_cs = 2;
+        }
+        break;
+      case 2: {  // search the unit, fetch the table entries of its first batch (one block per lane)
+        Scan sc = {0, 0, 0};
+        if (lane < S) {
+          sc.qa = (int)row(0)[lane];
+          sc.ql = (int)row(1)[lane] - sc.qa;
+          sc.cx = (int)row(2)[lane];
+        }
+        nxt = uniform_unit(locate(c_unit, sc));
+        if (nxt.s < 0) {
+          next_cs = kChainEnd;  // beyond the last unit: so is every later ticket
+        } else if (nxt.qlen > nxt.n) {
+          next_cs = kChainReady;  // invalid unit: nothing to resolve
+        } else {
+          if (lane < batch_blocks(0, unit_tiles(nxt), unit_blocks(nxt)))
+            row_fetch(3, p.table + (int64_t)nxt.s * p.table_stride + lane);
+          next_cs = 3;
+        }
+        break;
+      }
+      case 3: {  // check the entries, fetch their block list entries
+        const bool have = lane < batch_blocks(0, unit_tiles(nxt), unit_blocks(nxt));
+        const uint32_t id = have ? row(3)[lane] : 0u;
+        const bool lane_bad = have && !(id < (uint64_t)p.num_blocks);
+        nxt_bad = __builtin_amdgcn_readfirstlane(__any(lane_bad) ? 1u : 0u);
+        if (lane_bad) atomicCAS(p.status, 0, PIPELIVE_E_RANGE);  // never dereferenced: the batch's tokens are left out
+        if (have && !lane_bad) {
+          row_fetch(4, (const uint32_t *)(p.block_list + id));
+          row_fetch(5, (const uint32_t *)(p.block_list + id) + 1);
+        }
+        next_cs = 4;
+        break;
+      }
+      case 4: {
+        const bool have = lane < batch_blocks(0, unit_tiles(nxt), unit_blocks(nxt));
+        const bool ok = have && row(3)[lane] < (uint64_t)p.num_blocks;
+        nxt_addr = ok ? (((uint64_t)row(5)[lane] << 32) | row(4)[lane]) + p.layer_off : 0;
+        next_cs = kChainReady;
+        break;
+      }
+      default:
+        break;
+    }
+    cs = __builtin_amdgcn_readfirstlane(next_cs);
+  };
+  // After the tile's arithmetic, before its barrier (which publishes the mailbox).
+  auto chain_pass_on = [&]() {
+    if (cs == 0) {
+      if (tid == 0) mailbox = c_ticket;
+      cs = __builtin_amdgcn_readfirstlane(1);
+    }
+  };
+
+  // the first unit is the workgroup's own index; its search and addresses are waited for
+  Unit cur = uniform_unit(locate(blockIdx.x, scan_issue(0)));
+  uint64_t cur_addr = 0;
+  uint32_t cur_bad = 0;
+  if (cur.s >= 0 && cur.qlen <= cur.n) {
+    const uint64_t e = list_issue(cur, table_issue(cur), cur_bad);
+    cur_addr = e ? e + p.layer_off : 0;
+    cur_bad = __builtin_amdgcn_readfirstlane(cur_bad);
   }
-  if (s < 0) return;  // beyond the last unit (whole workgroup: the decision is the same in every wave)
-  // later query blocks attend to more tokens: hand them out first so the launch ends evenly
-  const int g = (int)(rem / nwb), wb = nwb - 1 - (int)(rem % nwb);
-  if (n > p.max_ctx) n = p.max_ctx;
+
+  // kept opaque so that it stays in registers instead of being rebuilt from scalars in every tile
+  u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
+  asm volatile("" : "+v"(ones_bits));
+  const bf16x8 ones = as_bf16x8(ones_bits);
+
+  // ---- global -> LDS copy of one tile: PER_THREAD LDS-direct loads per wave, each writing the 64
+  // consecutive 16-byte pieces [256 j + 64 w, +64) of the stage.  Which global piece a lane fetches
+  // for its position (the run, the byte inside it, for V the un-permuted piece) is fixed per thread;
+  // the KV head's offset joins the (scalar) sub-block address.
+  constexpr int RC = St::KRUN / 16;  // 16-byte pieces per run
+  uint32_t src_off[St::PER_THREAD];  // byte offset from the sub-block address of head 0's K run
+  bool second_half[St::PER_THREAD];  // the run belongs to the tile's second 16-token half (SB = 16 only)
+#pragma unroll
+  for (int j = 0; j < St::PER_THREAD; ++j) {
+    const int ci = tid + 256 * j;  // position in the stage
+    const int run = ci / RC, q = ci % RC;
+    const int is_v = run / St::HALVES, half = run % St::HALVES;
+    second_half[j] = half != 0;
+    int off = q * 16;
+    if (is_v) {
+      const int d = q / St::CPR, pos = q % St::CPR;
+      off = d * St::VROW + ((pos ^ St::swizzle(d)) * 16);
+    }
+    src_off[j] = (uint32_t)((is_v ? Hkv : 0) * St::KRUN + off);
+  }
+
+  while (cur.s >= 0) {
+  // (uniform by construction; said again so that everything derived from them is scalar)
+  const int s = __builtin_amdgcn_readfirstlane(cur.s), g = __builtin_amdgcn_readfirstlane(cur.g);
+  const int wb = __builtin_amdgcn_readfirstlane(cur.wb), q0 = __builtin_amdgcn_readfirstlane(cur.q0);
+  const int qlen = __builtin_amdgcn_readfirstlane(cur.qlen), n = __builtin_amdgcn_readfirstlane(cur.n);
+  cs = 0;  // start drawing the unit after this one
   if (qlen > n) {  // more queries than cached tokens: flag and skip
     if (tid == 0) atomicCAS(p.status, 0, PIPELIVE_E_INVAL);
-    return;
-  }
+  } else {
   // workgroup: the tiles its last query may see
   const int wg_tok0 = wb * WB;
   const int wg_ntok = min(WB, qlen - wg_tok0);
@@ -155,10 +322,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   f32x4 acc[ND][NQ];
   f32x4 lacc[NQ];  // every element: the column's running denominator
   float m[NQ];
-  // kept opaque so that it stays in registers instead of being rebuilt from scalars in every tile
-  u32x4 ones_bits = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
-  asm volatile("" : "+v"(ones_bits));
-  const bf16x8 ones = as_bf16x8(ones_bits);
 #pragma unroll
   for (int nq = 0; nq < NQ; ++nq) {
     m[nq] = -INFINITY;
@@ -167,25 +330,24 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     for (int c = 0; c < ND; ++c) acc[c][nq] = (f32x4){0.f, 0.f, 0.f, 0.f};
   }
 
-  // ---- block addresses, resolved 32 tiles at a time, one block per lane; the batch after the
-  // current one is resolved early so that the copies never wait for it
-  constexpr int TPB = BS >= kTile ? BS / kTile : 1;  // tiles per block (a 16-token block is half a tile)
+  // ---- block addresses, resolved 32 tiles at a time, one block per lane; batch 0 came with the unit,
+  // each later batch is resolved early so that the copies never wait for it
   const int n_blocks_seq = (wg_nkv + BS - 1) / BS;
   const uint32_t sub_bytes = SubBlock<BS>::bytes(Hkv, D);
-  uint64_t addr_a = 0, addr_b = 0;  // this lane's block address in the batches held (even, odd)
-  uint32_t bad_bits = 0;            // bit 0 / 1: the even / odd batch has an invalid table entry
+  const uint64_t head_off = (uint64_t)g * St::KRUN;  // the KV head's K run inside a sub-block
+  uint64_t addr_a = cur_addr, addr_b = 0;  // this lane's block address in the batches held (even, odd)
+  // bit 0 / 1: the even / odd batch has an invalid table entry (wave-uniform: kept in a scalar
+  // register, the tests cost no vector instruction)
+  uint32_t bad_bits = __builtin_amdgcn_readfirstlane(cur_bad);
   struct Resolved {
     uint64_t addr;
     uint32_t bad;
   };
   auto resolve = [&](int batch) -> Resolved {
     Resolved out = {0, 0};
-    const int t_lo = batch * kSubTiles;
-    if (t_lo >= nt_wg) return out;
-    const int t_hi = min(t_lo + kSubTiles, nt_wg);  // exclusive
-    const int first_blk = BS < kTile ? t_lo * 2 : t_lo / TPB;
-    const int last_blk = BS < kTile ? t_hi * 2 - 1 : (t_hi - 1) / TPB;
-    const int nblk = min(last_blk + 1, n_blocks_seq) - first_blk;
+    if (batch * kSubTiles >= nt_wg) return out;
+    const int first_blk = BS < kTile ? batch * kSubTiles * 2 : batch * kSubTiles / TPB;
+    const int nblk = batch_blocks(batch, nt_wg, n_blocks_seq);
     bool bad = false;
     if (lane < nblk) {
       const int id = p.table[(int64_t)s * p.table_stride + first_blk + lane];
@@ -203,7 +365,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     // use the address here, so that the wait for its load is placed here (once per 32 tiles) and not
     // in front of every later read of it, where it would also wait for the tile copies in flight
     asm volatile("" : "+v"(rv.addr));
-    // the flags are wave-uniform: kept in a scalar register, their tests cost no vector instruction
     if (batch & 1) {
       addr_b = rv.addr;
       bad_bits = __builtin_amdgcn_readfirstlane((bad_bits & 1u) | (rv.bad << 1));
@@ -219,38 +380,19 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     bad = (bad_bits >> (batch & 1)) & 1u;
     if (BS < kTile) {
       const int nblk = min((batch * kSubTiles + kSubTiles) * 2, n_blocks_seq) - batch * kSubTiles * 2;
-      a0 = readlane64(my, 2 * i);
-      a1 = (2 * i + 1 < nblk) ? readlane64(my, 2 * i + 1) : a0;
+      a0 = readlane64(my, 2 * i) + head_off;
+      a1 = (2 * i + 1 < nblk) ? readlane64(my, 2 * i + 1) + head_off : a0;
     } else {
       const int first_blk = batch * kSubTiles / TPB;
-      a0 = a1 = readlane64(my, t / TPB - first_blk) + (uint64_t)((t % TPB) * sub_bytes);
+      a0 = a1 = readlane64(my, t / TPB - first_blk) + (uint64_t)((t % TPB) * sub_bytes) + head_off;
     }
   };
 
-  // ---- global -> LDS copy of one tile: PER_THREAD LDS-direct loads per wave, each writing the 64
-  // consecutive 16-byte pieces [256 j + 64 w, +64) of the stage.  Which global piece a lane fetches
-  // for its position (the run, the byte inside it, for V the un-permuted piece) is fixed per thread.
-  constexpr int RC = St::KRUN / 16;  // 16-byte pieces per run
-  uint32_t src_off[St::PER_THREAD];  // byte offset from the run's sub-block address (head included)
-  bool second_half[St::PER_THREAD];  // the run belongs to the tile's second 16-token half (SB = 16 only)
-#pragma unroll
-  for (int j = 0; j < St::PER_THREAD; ++j) {
-    const int ci = tid + 256 * j;  // position in the stage
-    const int run = ci / RC, q = ci % RC;
-    const int is_v = run / St::HALVES, half = run % St::HALVES;
-    second_half[j] = half != 0;
-    int off = q * 16;
-    if (is_v) {
-      const int d = q / St::CPR, pos = q % St::CPR;
-      off = d * St::VROW + ((pos ^ St::swizzle(d)) * 16);
-    }
-    src_off[j] = (uint32_t)((is_v ? Hkv + g : g) * St::KRUN + off);
-  }
-  auto stage_load = [&](int t) {
+  auto stage_load = [&](int t) -> bool {  // false: nothing was issued
     uint64_t a0, a1;
     bool bad;
     tile_addr(t, a0, a1, bad);
-    if (__builtin_expect(bad, 0)) return;  // the batch is skipped by every wave: whatever the stage holds is never used
+    if (__builtin_expect(bad, 0)) return false;  // the batch is skipped by every wave: whatever the stage holds is never used
     lds_ptr st = (lds_ptr)lds + (t % kStages) * St::BYTES + w * 1024;
 #pragma unroll
     for (int j = 0; j < St::PER_THREAD; ++j) {
@@ -262,6 +404,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       }
       __builtin_amdgcn_global_load_lds((global_u4)(base + src_off[j]), (lds_u4)(st + 4096 * j), 16, 0, 0);
     }
+    return true;
   };
   // The barrier that ends a tile: this wave's copies of the next tile have landed and its LDS reads of
   // the current one are done; the copies of the tile after next, issued a moment ago, may still be
@@ -323,7 +466,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll
     for (int c = 0; c < ND; ++c) vreg[c] = *(lds_u4)(st + vlane + 16 * c * St::VROW);
     __builtin_amdgcn_sched_barrier(0);
-    PTRACE(1);  // K read, QK, V requests
 
     // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
     float x[NQ][8];
@@ -388,7 +530,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         for (int i = 0; i < 4; ++i) ph[nq][i] = pack_bf16_rne(pv[2 * i], pv[2 * i + 1]);
       }
     }
-    PTRACE(2);  // softmax
     // V of tokens past the wave's readable range must be zero (0 * NaN is NaN)
     if (MASK) {
       u32x4 vmask;
@@ -423,30 +564,29 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
             acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vreg[c + u]), as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
       }
     }
-    PTRACE(5);  // V read + PV
   };
 
   // ---- the tile loop: copies are issued two tiles ahead of the arithmetic and need to have landed
   // one tile ahead, one barrier per tile.  Stage (t+2) % 3 was last read for tile t-1, which every
   // wave left before the barrier that ended iteration t-1.
-  resolve_into_slot(0);
   resolve_into_slot(1);
   stage_load(0);
   if (nt_wg > 1) stage_load(1);
   tile_barrier(false);
   auto step = [&](int t, auto mask_tag) {
-    PTRACE_START();
-    const bool more = t + 2 < nt_wg;
-    if (__builtin_expect(more, 1)) stage_load(t + 2);
+    // (its loads are older than this tile's copies: the barrier's count still holds; the test keeps
+    // the chain's code and its waits off the path of the tiles that have nothing left to step)
+    const bool stepping = __builtin_amdgcn_readfirstlane(cs) < kChainReady;
+    if (__builtin_expect(stepping, 0)) chain_step();
+    bool more = t + 2 < nt_wg;
+    if (__builtin_expect(more, 1)) more = stage_load(t + 2);
     const int batch = t / kSubTiles;
     const bool bad = (bad_bits >> (batch & 1)) & 1u;
     // a quarter into a batch the slot of the batch before it is free: resolve the batch after it
     if (__builtin_expect(t % kSubTiles == 8 && batch >= 1, 0)) resolve_into_slot(batch + 1);
-    PTRACE(0);  // issue of the copies
     if (__builtin_expect(t < nt_w && !bad, 1)) compute(t, mask_tag);
-    PTRACE(6);
+    if (__builtin_expect(stepping, 0)) chain_pass_on();
     tile_barrier(more);  // tile t+1 must be in LDS past the barrier; the copies of tile t+2 may still fly
-    PTRACE(7);           // wait for the copies + barrier
   };
   // tiles wholly below the workgroup's first query need no mask in any wave; the few tiles on the
   // diagonal take the masked form (two loops, so that each form is generated once)
@@ -456,7 +596,6 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 #pragma unroll 1
   for (int t = nt_plain; t < nt_wg; ++t) step(t, std::true_type{});
 
-  PTRACE_FLUSH(nt_wg);
 
   // ---- normalise and store: lane (qg, r) holds O[column r of block nq][16c + 4qg + i]
 #pragma unroll
@@ -483,24 +622,65 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       }
     }
   }
+  }  // a valid unit
+
+  // whatever is left of the next unit's steps (short units): now with their latency in the open
+  while (cs < kChainReady) {
+    chain_step();
+    chain_pass_on();
+    __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0): the rows have landed, the mailbox is written
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+  if (cs == kChainReady) {
+    cur = nxt;
+    cur_addr = nxt_addr;
+    cur_bad = nxt_bad;
+  } else {
+    cur.s = -1;
+  }
+  }  // units of this workgroup
+
+  // the last workgroup to leave re-arms both counters for the next launch
+  if (tid == 0) {
+    const int done = atomicAdd(p.finished, 1);
+    if (done == grid - 1) {
+      atomicExch(p.ticket, 0);
+      atomicExch(p.finished, 0);
+    }
+  }
+}
+
+// Persistent launch: as many workgroups as the device holds at once (never more than there are
+// units); each takes the unit of its own index first and draws the following ones from the ticket
+// counter.
+template <int D, int BS, bool PAIR>
+int resident_workgroups() {
+  static int cached = 0;
+  if (cached == 0) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, attn_prefill_kernel<D, BS, kPrefillNQ, PAIR>, 256, 0) !=
+            hipSuccess ||
+        nb < 1)
+      nb = 1;
+    cached = nb * device_cu_count();
+  }
+  return cached;
 }
 
 template <int D, int BS>
 hipError_t launch_t(const PrefillParams &p, hipStream_t st) {
-  if (p.out_dtype == PIPELIVE_OUT_F32)
-    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, true>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
-  else
-    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, false>), dim3((unsigned)p.num_units), dim3(256), 0, st, p);
+  if (p.out_dtype == PIPELIVE_OUT_F32) {
+    const int grid = p.num_units < resident_workgroups<D, BS, true>() ? p.num_units : resident_workgroups<D, BS, true>();
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  } else {
+    const int grid = p.num_units < resident_workgroups<D, BS, false>() ? p.num_units : resident_workgroups<D, BS, false>();
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
-
-#ifdef PIPELIVE_PREFILL_TRACE
-extern "C" int pipelive_dev_prefill_trace(long long *out16) {
-  return (int)hipMemcpyFromSymbol(out16, HIP_SYMBOL(g_prefill_trace), 16 * sizeof(long long));
-}
-#endif
 
 hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st) {
 #define X(d, b) \

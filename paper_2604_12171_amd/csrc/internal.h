@@ -13,7 +13,9 @@ struct DevState {
   unsigned long long n_acc;      // tokens marked since the last complete drain
   unsigned long long t_applied;  // T_applied
   int32_t status;                // sticky: first PIPELIVE_E_* seen on the device
-  int32_t pad_[11];
+  int32_t prefill_ticket;        // work distribution of the prefill kernel: both are zero whenever no
+  int32_t prefill_finished;      // prefill launch of this region is running
+  int32_t pad_[9];
 };
 static_assert(sizeof(DevState) == 64, "DevState layout");
 constexpr size_t kSnapOffset = 256;
@@ -84,9 +86,11 @@ struct PrefillParams {
   int32_t num_seqs, max_ctx;
   int32_t Hq, Hkv, G;
   float scale_log2;
-  int32_t num_units;  // workgroups launched (an upper bound on the units)
+  int32_t num_units;  // an upper bound on the units (the ragged split is only known on the device)
   int64_t num_blocks;
   int32_t *status;
+  int32_t *ticket;    // units drawn beyond the first one of every workgroup; zero between launches
+  int32_t *finished;  // workgroups that have left; the last one zeroes both
 };
 hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st);
 

@@ -521,7 +521,12 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
   }
 }
 
-__global__ void clear_status_kernel(DevState *st) { st->status = 0; }
+// also re-arms the prefill kernel's work counters (they are zero already unless a launch was cut short)
+__global__ void clear_status_kernel(DevState *st) {
+  st->status = 0;
+  st->prefill_ticket = 0;
+  st->prefill_finished = 0;
+}
 
 XferArgs make_xfer(const pipelive_kv *kv, const LayerList &layers, const int32_t *dst_map) {
   XferArgs a;
