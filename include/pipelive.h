@@ -170,6 +170,11 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
  * other arguments as for pipelive_paged_attn_decode; no workspace is needed.
  * A sequence with more queries than cached tokens sets the status word
  * (PIPELIVE_E_INVAL) and its rows are not written.  Asynchronous.
+ * The kernel hands out its work through two counters in the region's
+ * dev_state (zero between launches; the last workgroup re-arms them, so
+ * replaying a captured launch is fine): two prefill calls on the same region
+ * must not run at the same time (e.g. on two streams).  After a launch that
+ * was cut short, pipelive_kv_clear_status() re-arms the counters.
  */
 int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
                                     int32_t out_dtype, const int32_t *block_table,

@@ -259,8 +259,8 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
   p.G = p.Hq / p.Hkv;
   const float sc = scale > 0.f ? scale : 1.0f / sqrtf((float)kv->d.head_dim);
   p.scale_log2 = sc * 1.4426950408889634f;
-  // one workgroup per (sequence, KV head, block of 4 * QB query tokens); the ragged split is only
-  // known on the device, so launch the upper bound and let the surplus workgroups exit
+  // units = (sequence, KV head, block of 4 * QB query tokens); the ragged split is only known on the
+  // device, so the kernel gets an upper bound and stops at the first ticket that names no unit
   const int wb = 4 * ((kPrefillNQ * 16) / p.G);
   const int64_t units = (int64_t)p.Hkv * ((total_q + wb - 1) / wb + num_seqs);
   if (units > (1ll << 30)) return PIPELIVE_E_INVAL;

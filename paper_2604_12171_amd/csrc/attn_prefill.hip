@@ -2,19 +2,25 @@
 // compute-bound stage (paper Sec. 2 "LLM Inference": prompt tokens are
 // processed in parallel) over the same block-list KV layout as decode.
 //
-// Work unit = (sequence, KV head, block of 4*QB consecutive query tokens), one
-// per workgroup; wave w of it owns the QB tokens [w*QB, (w+1)*QB) of the block.
-// A wave's NQ*16 score columns are its QB tokens x the G query heads of the KV
-// head (column = token * G + head).  The workgroup walks the 32-token KV tiles
-// that its last query may see; each tile's K and V of the KV head (two
+// Work unit = (sequence, KV head, block of 4*QB consecutive query tokens); wave
+// w of the workgroup that takes it owns the QB tokens [w*QB, (w+1)*QB) of the
+// block.  A wave's NQ*16 score columns are its QB tokens x the G query heads of
+// the KV head (column = token * G + head).  The kernel is persistent: as many
+// workgroups as the device holds at once; each takes the unit of its own index
+// first and then draws units from a ticket counter, and while it works on one
+// unit it already draws, searches and resolves the next (one step per tile, the
+// loads going straight into a few LDS rows), so that a unit starts with its
+// block addresses in hand.  For a unit the workgroup walks the 32-token KV
+// tiles that its last query may see; each tile's K and V of the KV head (two
 // contiguous runs of the in-block layout) are copied once from global memory
 // into a ring of three LDS stages by LDS-direct loads (global_load_lds_dwordx4:
 // no staging registers), issued two tiles ahead of the arithmetic, and all
 // four waves take their MFMA operands from there.  Per tile a wave computes
 // S^T = K Q^T for its columns, applies the causal mask by predicate, runs the
-// online softmax per column and accumulates O^T += V^T P^T with P split into
-// two bf16 terms.  A wave whose queries cannot see a tile, or that has no
-// queries at all, still takes part in the copies and barriers.
+// online softmax per column and accumulates O^T += V^T P^T (P as a pair of bf16
+// terms for fp32 output, as one for bf16 output).  A wave whose queries cannot
+// see a tile, or that has no queries at all, still takes part in the copies and
+// barriers.
 #include <type_traits>
 
 #include "attn_common.h"
