@@ -128,6 +128,41 @@ def test_prefill_many_sequences_multi_chunk_unit_search():
     assert P.pipelive_kv_read_state(dev).status == 0
 
 
+def test_prefill_more_units_than_resident_workgroups_and_relaunch():
+    """Enough (sequence, head, query block) units that every resident workgroup has to draw further
+    ones from the ticket counter (ragged lengths, chunks and full prompts); a second launch must find
+    the counters re-armed and give the same bits."""
+    rng = np.random.default_rng(11)
+    S, Hq, Hkv, D, bs = 40, 16, 4, 64, 16
+    ctx = rng.integers(150, 420, size=S)
+    qlen = np.where(rng.random(S) < 0.5, ctx, np.minimum(ctx, rng.integers(1, 200, size=S)))
+    cfg = pin.StageConfig("pf", 1, Hq, Hkv, D, bs, S, 0, 0)
+    batch = _batch(cfg, ctx)
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
+    total_q = int(qo[-1])
+    units = Hkv * int(np.sum((qlen + 31) // 32))          # 32 query tokens per unit at G = 4
+    assert units > 2 * 256 * 2                            # more than two per resident workgroup
+    q = pin.f32_to_bf16_bits(rng.standard_normal((total_q, Hq, D)).astype(np.float32))
+    q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    t, c, o = torch.from_numpy(batch.table).cuda(), torch.from_numpy(batch.ctx_lens).cuda(), torch.from_numpy(qo).cuda()
+    outs = []
+    for _ in range(2):
+        out = torch.full((total_q, Hq, D), float("nan"), dtype=torch.float32, device="cuda")
+        P.pipelive_paged_attn_prefill(dev, 0, q_d, out, t, c, o, total_q)
+        torch.cuda.synchronize()
+        outs.append(out.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+    got = outs[0]
+    assert np.isfinite(got).all()
+    ref = host.attn_prefill(0, q, batch.table, batch.ctx_lens, qo, nthreads=8)
+    for s in range(S):
+        ma, rl = attn_errors(got[qo[s]:qo[s + 1]], ref[qo[s]:qo[s + 1]])
+        assert ma <= MAX_ABS and rl <= REL_L2, (s, ma, rl)
+    assert P.pipelive_kv_read_state(dev).status == 0
+
+
 def test_prefill_bad_table_entry_sets_status_and_spares_the_others():
     ctx, qlen = [100, 64, 200], [100, 10, 50]
     cfg = pin.StageConfig("pf", 1, 8, 2, 128, 16, 3, 0, 0)
