@@ -133,9 +133,10 @@ def test_prefill_more_units_than_resident_workgroups_and_relaunch():
     ones from the ticket counter (ragged lengths, chunks and full prompts); a second launch must find
     the counters re-armed and give the same bits."""
     rng = np.random.default_rng(11)
-    S, Hq, Hkv, D, bs = 40, 16, 4, 64, 16
-    ctx = rng.integers(150, 420, size=S)
-    qlen = np.where(rng.random(S) < 0.5, ctx, np.minimum(ctx, rng.integers(1, 200, size=S)))
+    S, Hq, Hkv, D, bs = 100, 16, 4, 64, 16                # more than 64 sequences: the drawn units' search spans chunks
+    ctx = rng.integers(60, 260, size=S)
+    qlen = np.where(rng.random(S) < 0.5, ctx, np.minimum(ctx, rng.integers(1, 120, size=S)))
+    qlen[5::17] = 0
     cfg = pin.StageConfig("pf", 1, Hq, Hkv, D, bs, S, 0, 0)
     batch = _batch(cfg, ctx)
     host, dev = make_pair(cfg, batch, SEED)
