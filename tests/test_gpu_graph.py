@@ -29,6 +29,8 @@ class _Side:
         self.v = torch.zeros((L, S, Hkv, D), dtype=torch.bfloat16, device="cuda")
         self.q = torch.zeros((L, S, Hq, D), dtype=torch.bfloat16, device="cuda")
         self.out = torch.zeros((L, S, Hq, D), dtype=torch.float32, device="cuda")
+        self.pf_out = torch.zeros((S, Hq, D), dtype=torch.float32, device="cuda")
+        self.q_off = torch.arange(S + 1, dtype=torch.int32, device="cuda")   # one query row per sequence
         self.pos = torch.zeros(S, dtype=torch.int32, device="cuda")
         self.ctx = torch.zeros(S, dtype=torch.int32, device="cuda")
         cap = 64 + 256 + S * (4 + L * self.src.unit_bytes) + 64
@@ -42,6 +44,9 @@ class _Side:
             P.pipelive_kv_append(self.src, l, self.k[l], self.v[l], table, self.pos, mark=True, count_tokens=(l == 0))
             P.pipelive_paged_attn_decode(self.src, l, self.q[l], self.out[l], table, self.ctx, max_ctx=int(table.shape[1]) * self.src.bs,
                                          workspace=self.ws)
+        # the persistent prefill kernel re-arms its work counters itself: it must replay as well
+        P.pipelive_paged_attn_prefill(self.src, 0, self.q[0], self.pf_out, table, self.ctx, self.q_off, self.q.shape[1],
+                                      max_ctx=int(table.shape[1]) * self.src.bs)
         P.pipelive_kv_patch_collect(self.src, layers, self.patch)
         P.pipelive_kv_patch_apply(self.tgt, layers, self.patch)
 
@@ -86,6 +91,8 @@ def test_decode_step_and_patch_cycle_replay_from_a_graph():
         b.step(table)
         torch.cuda.synchronize()
         assert torch.equal(a.out, b.out), step
+        assert torch.equal(a.pf_out, b.pf_out), step
+        assert torch.allclose(a.pf_out, a.out[0], atol=1e-5, rtol=1e-5), step    # one-query prefill = decode
         assert torch.isfinite(a.out).all()
         assert torch.equal(a.patch, b.patch), step
         for l in range(L):
