@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   };
   auto locate = [&](int unit, Scan first) -> Unit {
     Unit u = {-1, 0, 0, 0, 0, 0};
-    int64_t carry = 0;
+    int carry = 0;  // the host keeps the number of units below 2^30
     for (int base = 0; base < S && u.s < 0; base += 64) {
       const Scan sc = base == 0 ? first : scan_issue(base);
       const int nb = sc.ql > 0 ? (sc.ql + WB - 1) / WB : 0;
@@ -101,11 +101,12 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       const uint64_t bal = __ballot(carry + inc > unit);  // first sequence whose range holds it
       if (bal) {
         const int k = __ffsll((long long)bal) - 1;
-        const int nwb = __builtin_amdgcn_readlane(nb, k);
-        const int64_t rem = unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k));
+        const uint32_t nwb = (uint32_t)__builtin_amdgcn_readlane(nb, k);
+        const uint32_t rem =
+            (uint32_t)(unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k)));
         u.s = base + k;
         u.g = (int)(rem / nwb);
-        u.wb = nwb - 1 - (int)(rem % nwb);
+        u.wb = (int)(nwb - 1 - rem % nwb);
         u.q0 = __builtin_amdgcn_readlane(sc.qa, k);
         u.qlen = __builtin_amdgcn_readlane(sc.ql, k);
         u.n = min(__builtin_amdgcn_readlane(sc.cx, k), p.max_ctx);
