@@ -6,11 +6,13 @@
 //           free ids in the head [0, B_new) (prefix sums of popcounts), and
 //           whether any dirty bit is pending.  It changes nothing.
 // check   : every used table entry must be a live id below B.
-// commit  : copy block T[k] -> F[k] in every layer group, build remap[],
-//           rewrite the tables, move the live bits.  Sources and destinations
+// commit  : two launches: copy block T[k] -> F[k] in every layer group and
+//           build remap[]; then rewrite the tables and move the live bits.  Sources and destinations
 //           are disjoint id sets, so the copy needs no ordering.  The commit
 //           kernels are queued right behind the plan and read its verdict on
 //           the device: a refused resize changes nothing.
+#include <string.h>
+
 #include "internal.h"
 #include "kv_copy.h"
 #include "scan.h"
@@ -112,6 +114,29 @@ __global__ void table_check_kernel(const u64 *live, int64_t B, TableRef t, Resiz
   if (bad) atomicOr((u64 *)&plan->bad_table, 1ull);
 }
 
+// remap[b] for b in [0,B): identity if live and kept, -1 if not live; moved ids are written from the
+// move list (disjoint from the first set).  Index i runs over [0, B + n_moved).  Reads the live bitmap
+// as it was before the resize: the kernels that call this run before the one that moves the live bits.
+struct RemapArgs {
+  const u64 *live;
+  int64_t B, B_new;
+  const int32_t *move_src, *move_dst;
+  int32_t *remap;
+};
+__device__ __forceinline__ void remap_all(const RemapArgs &r, int64_t n_moved) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < r.B + n_moved; i += stride) {
+    if (i < r.B) {
+      const bool lv = (r.live[i >> 6] >> (i & 63)) & 1ull;
+      if (!lv) r.remap[i] = -1;
+      else if (i < r.B_new) r.remap[i] = (int32_t)i;
+    } else {
+      const int64_t k = i - r.B;
+      r.remap[r.move_src[k]] = r.move_dst[k];
+    }
+  }
+}
+
 struct MoveArgs {
   const uint64_t *block_list;
   int64_t capacity;
@@ -120,10 +145,13 @@ struct MoveArgs {
   const int32_t *move_src, *move_dst;
   const ResizePlanOut *plan;  // n_moved and the verdict
   int64_t B_new;
+  RemapArgs remap;
 };
 
+// The copies of a shrink; the same launch also writes remap[] (a megabyte next to gigabytes).
 __global__ __launch_bounds__(kCopyThreads) void move_kernel(MoveArgs a) {
   if (!plan_ok(a.plan, a.B_new)) return;
+  remap_all(a.remap, a.plan->n_moved);
   const int64_t n_items = a.plan->n_moved * a.groups * a.subs_per_block;
   for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
     const uint32_t sub = (uint32_t)(item % a.subs_per_block);
@@ -141,54 +169,53 @@ __global__ __launch_bounds__(kCopyThreads) void move_kernel(MoveArgs a) {
 
 // Per-block backing: a move exchanges the two block_list entries of every
 // group instead of copying bytes (the sets of sources and targets are
-// disjoint, so the exchanges are independent).
+// disjoint, so the exchanges are independent).  Writes remap[] as well.
 __global__ void swap_kernel(uint64_t *block_list, int64_t capacity, int32_t groups,
-                            const ResizePlanOut *plan, int64_t B_new, const int32_t *move_src,
-                            const int32_t *move_dst) {
-  const int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-  if (!plan_ok(plan, B_new) || i >= plan->n_moved * groups) return;
-  uint64_t *bl = block_list + (i % groups) * capacity;
-  const int64_t k = i / groups;
-  const uint64_t a = bl[move_src[k]], b = bl[move_dst[k]];
-  bl[move_src[k]] = b;
-  bl[move_dst[k]] = a;
-}
-
-// remap[b] for b in [0,B): identity if live and kept, -1 if not live; moved
-// ids are written from the move list (disjoint from the first set).
-__global__ void remap_kernel(const u64 *live, int64_t B, int64_t B_new, const ResizePlanOut *plan,
-                             const int32_t *move_src, const int32_t *move_dst, int32_t *remap) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (!plan_ok(plan, B_new)) return;
+                            const ResizePlanOut *plan, RemapArgs r) {
+  if (!plan_ok(plan, r.B_new)) return;
   const int64_t n_moved = plan->n_moved;
-  if (i < B) {
-    const bool lv = (live[i >> 6] >> (i & 63)) & 1ull;
-    if (!lv) remap[i] = -1;
-    else if (i < B_new) remap[i] = (int32_t)i;
-  } else if (i < B + n_moved) {
-    const int64_t k = i - B;
-    remap[move_src[k]] = move_dst[k];
+  remap_all(r, n_moved);
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_moved * groups; i += stride) {
+    uint64_t *bl = block_list + (i % groups) * capacity;
+    const int64_t k = i / groups;
+    const uint64_t a = bl[r.move_src[k]], b = bl[r.move_dst[k]];
+    bl[r.move_src[k]] = b;
+    bl[r.move_dst[k]] = a;
   }
 }
 
-__global__ void table_remap_kernel(TableRef t, const int32_t *remap, const ResizePlanOut *plan,
-                                   int64_t B_new) {
-  if (!plan_ok(plan, B_new)) return;
-  const int row = blockIdx.x;
-  const int used = t.used[row];
-  for (int i = threadIdx.x; i < used; i += blockDim.x) {
-    int32_t *e = &t.table[(int64_t)row * t.stride + i];
-    *e = remap[*e];
-  }
-}
-
-__global__ void live_update_kernel(u64 *live, const ResizePlanOut *plan, int64_t B_new,
-                                   const int32_t *move_src, const int32_t *move_dst) {
-  const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (plan_ok(plan, B_new) && k < plan->n_moved) {
-    const int32_t s = move_src[k], d = move_dst[k];
-    atomicAnd(&live[s >> 6], ~(1ull << (s & 63)));
-    atomicOr(&live[d >> 6], 1ull << (d & 63));
+// Last kernel of a shrink: every used table entry follows remap[] (one workgroup per table row, all
+// tables in one launch), and the workgroups behind them move the live bits of the moved ids.
+struct FinishArgs {
+  TableRef t[PIPELIVE_MAX_TABLES];
+  int32_t row_end[PIPELIVE_MAX_TABLES];  // running sum of the tables' rows
+  int32_t n_tables, total_rows;
+  const int32_t *remap;
+  const ResizePlanOut *plan;
+  int64_t B_new;
+  u64 *live;
+  const int32_t *move_src, *move_dst;
+};
+__global__ __launch_bounds__(256) void finish_kernel(FinishArgs a) {
+  if (!plan_ok(a.plan, a.B_new)) return;
+  if ((int)blockIdx.x < a.total_rows) {
+    int ti = 0;
+    while (ti + 1 < a.n_tables && (int)blockIdx.x >= a.row_end[ti]) ++ti;
+    const TableRef &t = a.t[ti];
+    const int row = (int)blockIdx.x - (ti ? a.row_end[ti - 1] : 0);
+    const int used = t.used[row];
+    for (int i = threadIdx.x; i < used; i += blockDim.x) {
+      int32_t *e = &t.table[(int64_t)row * t.stride + i];
+      *e = a.remap[*e];
+    }
+  } else {
+    const int64_t k = (int64_t)((int)blockIdx.x - a.total_rows) * blockDim.x + threadIdx.x;
+    if (k < a.plan->n_moved) {
+      const int32_t s = a.move_src[k], d = a.move_dst[k];
+      atomicAnd(&a.live[s >> 6], ~(1ull << (s & 63)));
+      atomicOr(&a.live[d >> 6], 1ull << (d & 63));
+    }
   }
 }
 
@@ -226,17 +253,25 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
                                 const ResizePlanOut *plan, const int32_t *move_src,
                                 const int32_t *move_dst, int32_t *remap, const TableRef *tables,
                                 int n_tables, hipStream_t st) {
-  // grids are sized for the most a shrink can move, B - B_new blocks: the count itself is read from
-  // the plan on the device
+  // Two launches, sized for the most a shrink can move (B - B_new blocks; the count itself is read
+  // from the plan on the device): the moves with remap[], then the tables with the live bits.
   hipError_t e;
   const int64_t max_moved = B - B_new;
-  if (max_moved > 0 && kv->d.block_backing == PIPELIVE_BACKING_PER_BLOCK) {
-    const int64_t n = max_moved * kv->groups;
+  if (max_moved <= 0) return hipSuccess;
+  RemapArgs r;
+  r.live = (const u64 *)kv->d.live_bitmap;
+  r.B = B;
+  r.B_new = B_new;
+  r.move_src = move_src;
+  r.move_dst = move_dst;
+  r.remap = remap;
+  if (kv->d.block_backing == PIPELIVE_BACKING_PER_BLOCK) {
+    const int64_t n = B + max_moved;  // remap entries: the larger of the two index spaces
     hipLaunchKernelGGL(swap_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
                        const_cast<uint64_t *>(kv->d.block_list), kv->d.capacity_blocks,
-                       (int32_t)kv->groups, plan, B_new, move_src, move_dst);
+                       (int32_t)kv->groups, plan, r);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-  } else if (max_moved > 0) {
+  } else {
     MoveArgs a;
     a.block_list = kv->d.block_list;
     a.capacity = kv->d.capacity_blocks;
@@ -248,32 +283,33 @@ hipError_t launch_resize_commit(const pipelive_kv *kv, int64_t B, int64_t B_new,
     a.move_dst = move_dst;
     a.plan = plan;
     a.B_new = B_new;
+    a.remap = r;
     const int64_t max_items = max_moved * kv->groups * a.subs_per_block;
     const int64_t max_grid = (int64_t)device_cu_count() * copy_wgs_per_cu();
     const int grid = (int)(max_items < max_grid ? max_items : max_grid);
     hipLaunchKernelGGL(move_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
   }
-  {
-    const int64_t n = B + (max_moved > 0 ? max_moved : 0);
-    if (n > 0) {
-      hipLaunchKernelGGL(remap_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                         (const u64 *)kv->d.live_bitmap, B, B_new, plan, move_src, move_dst, remap);
-      if ((e = hipGetLastError()) != hipSuccess) return e;
-    }
-  }
+  FinishArgs f;
+  memset(&f, 0, sizeof f);
+  int rows = 0;
   for (int t = 0; t < n_tables; ++t) {
     if (tables[t].rows <= 0) continue;
-    hipLaunchKernelGGL(table_remap_kernel, dim3(tables[t].rows), dim3(256), 0, st, tables[t],
-                       (const int32_t *)remap, plan, B_new);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    f.t[f.n_tables] = tables[t];
+    rows += tables[t].rows;
+    f.row_end[f.n_tables] = rows;
+    ++f.n_tables;
   }
-  if (max_moved > 0) {
-    hipLaunchKernelGGL(live_update_kernel, dim3((unsigned)((max_moved + 255) / 256)), dim3(256), 0,
-                       st, (u64 *)kv->d.live_bitmap, plan, B_new, move_src, move_dst);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-  }
-  return hipSuccess;
+  f.total_rows = rows;
+  f.remap = remap;
+  f.plan = plan;
+  f.B_new = B_new;
+  f.live = (u64 *)kv->d.live_bitmap;
+  f.move_src = move_src;
+  f.move_dst = move_dst;
+  const int64_t grid = rows + (max_moved + 255) / 256;
+  hipLaunchKernelGGL(finish_kernel, dim3((unsigned)grid), dim3(256), 0, st, f);
+  return hipGetLastError();
 }
 
 hipError_t launch_grow(const pipelive_kv *kv, int64_t B, int64_t B_new, int32_t *remap,
