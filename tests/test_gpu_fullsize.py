@@ -362,13 +362,15 @@ def test_stage8b_stacked_per_block_pool_decode_shrink_release():
     torch.cuda.empty_cache()
 
 
-def test_prefill_chunk_in_bench_configuration():
-    """bench.py's chunked-prefill case (16 sequences, a 512-token chunk on 4096 cached tokens, 8B-stage heads).
-    A prefill row is the decode of its token over the context it may see, so sampled rows are checked against
-    the oracle's *decode* attention on a context truncated at the row's position."""
+@pytest.mark.parametrize("case", [("chunk512_of_4096", 16, 4096, 512), ("prompt512", 64, 512, 512)])
+def test_prefill_in_bench_configuration(case):
+    """bench.py's prefill cases with the 8B stage's heads: a 512-token chunk on 4096 cached tokens (16
+    sequences) and 64 prompts of 512 tokens.  A prefill row is the decode of its token over the context it
+    may see, so sampled rows are checked against the oracle's *decode* attention on a context truncated at
+    the row's position."""
     base = pin.CONFIGS["stage8b"]
-    S, ctx_len, q_len = 16, 4096, 512
-    cfg = pin.StageConfig("chunk512_of_4096", 1, base.num_q_heads, base.num_kv_heads, base.head_dim,
+    tag, S, ctx_len, q_len = case
+    cfg = pin.StageConfig(tag, 1, base.num_q_heads, base.num_kv_heads, base.head_dim,
                           base.block_tokens, S, ctx_len, ctx_len)
     batch = pin.draw_batch(cfg, SEED, pool_factor=1.25)
     cap = batch.num_blocks
@@ -393,7 +395,7 @@ def test_prefill_chunk_in_bench_configuration():
     assert np.isfinite(got16).all()
     worst = (0.0, 0.0)
     worst16 = (0.0, 0.0)
-    for s in (0, 5, 11, 15):
+    for s in (0, 5, 11, S - 1):
         u = int(batch.used[s])
         host = oracle.HostKV(1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, u,
                              layout=cfg.layout, arenas=2, fill_bits=pin.BF16_NAN)
