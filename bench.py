@@ -298,6 +298,22 @@ def main():
         st = P.pipelive_kv_read_state(target)
         if st.status != 0 or P.pipelive_kv_read_state(region).status != 0:
             raise RuntimeError("device status word set during the bench")
+        # context for the HBM fractions above: what a plain device-to-device copy of the same size class
+        # reaches on this part (torch's copy kernel over the patch buffer; read + write bytes counted)
+        half = (bulk_cap // 2) & ~0xFFF
+        tcp = []
+        for it in range(11):
+            e0, e1 = ev(), ev()
+            e0.record()
+            bulk_patch[half:2 * half].copy_(bulk_patch[:half])
+            e1.record()
+            torch.cuda.synchronize()
+            if it:
+                tcp.append(e0.elapsed_time(e1))
+        tcpm = sorted(tcp)[len(tcp) // 2]
+        result["copy_ceiling"] = {"kind": "torch device-to-device copy, read + write", "bytes": int(half),
+                                  "us": round(tcpm * 1e3, 1), "GBps": round(2 * half / (tcpm * 1e-3) / 1e9, 1),
+                                  "frac_of_peak": round(2 * half / (tcpm * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
         del bulk_patch
 
     # ---------------- steady-state decode at slot granularity (the paper's own unit): every layer
