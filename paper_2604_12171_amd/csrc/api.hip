@@ -39,17 +39,8 @@ int device_cu_count() {
   }
   return g_cu_count;
 }
-int copy_wgs_per_cu() {
-  static int v = 0;
-  if (v == 0) {
-    v = 16;
-    if (const char *e = getenv("PIPELIVE_COPY_WGS_PER_CU")) {  // tuning aid
-      const int x = atoi(e);
-      if (x >= 1 && x <= 64) v = x;
-    }
-  }
-  return v;
-}
+// persistent copy kernels: 16 workgroups per CU, the setting the launch-shape sweeps of the copies settled on
+int copy_wgs_per_cu() { return 16; }
 }  // namespace pipelive
 
 extern "C" {
@@ -147,15 +138,7 @@ static bool attn_shape(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ct
     // list, partial records) then has to wait in.
     int wpc = attn_waves_per_cu(kv->d.head_dim, kv->d.block_tokens);
     if (wpc > 4) wpc = 4;
-    if (const char *e = getenv("PIPELIVE_ATTN_WAVES_PER_CU")) {  // tuning aid
-      const int v = atoi(e);
-      if (v >= 1 && v <= 16) wpc = v;
-    }
-    int64_t resident = (int64_t)device_cu_count() * wpc;
-    if (const char *e = getenv("PIPELIVE_ATTN_WAVES")) {  // tuning aid: absolute number of waves
-      const int v = atoi(e);
-      if (v >= 4 && v <= 65536) resident = v;
-    }
+    const int64_t resident = (int64_t)device_cu_count() * wpc;
     int64_t nw = upper < resident ? upper : resident;
     out->num_waves = (int32_t)(nw < 1 ? 1 : nw);
     out->tiles_per_wave = 0;
