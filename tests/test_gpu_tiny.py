@@ -216,3 +216,42 @@ def test_device_status_word_on_bad_ids():
     P.pipelive_kv_clear_status(small)
     P.pipelive_kv_patch_apply(small, [0, 1], patch)
     assert P.pipelive_kv_read_state(small).status == P.E_INVAL
+
+
+@pytest.mark.parametrize("backing", ["arena", "vmm"])
+def test_resize_with_no_table_and_with_several_tables(backing):
+    """The last kernel of a shrink rewrites every table in one launch and moves the live bits: none, and
+    three tables of different shapes (the batch's rows split in two, plus a table that shares blocks with
+    them and holds rows without entries)."""
+    cfg = pin.CONFIGS["tiny"]
+    B = 128
+    batch = pin.draw_batch(cfg, SEED, num_blocks=B)
+    for n_tables in (0, 3):
+        host, dev = make_pair(cfg, batch, SEED, backing=backing)
+        fill_pair(cfg, batch, SEED, host, dev)
+        half = cfg.num_seqs // 2
+        t0, u0 = batch.table[:half].copy(), batch.used[:half].copy()
+        t1 = np.ascontiguousarray(np.pad(batch.table[half:], ((0, 0), (0, 5)), constant_values=pin.TABLE_FILL))
+        u1 = batch.used[half:].copy()
+        t2 = np.full((4, 3), pin.TABLE_FILL, dtype=np.int32)      # prefix sharing: first blocks of four sequences
+        u2 = np.zeros(4, dtype=np.int32)
+        for k, srow in enumerate((0, half, 1)):
+            n = min(3, int(batch.used[srow]))
+            t2[k, :n] = batch.table[srow, :n]
+            u2[k] = n                                           # row 3 stays empty
+        tabs_h = [t0, t1, t2][:n_tables]
+        used_h = [u0, u1, u2][:n_tables]
+        tabs_d = [torch.from_numpy(t.copy()).cuda() for t in tabs_h]
+        used_d = [torch.from_numpy(u.copy()).cuda() for u in used_h]
+        rc_h, remap_h, res_h = host.resize(96, tabs_h, used_h)
+        remap_d = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+        rc_d, res_d = P.pipelive_kv_resize(dev, 96, tabs_d, used_d, remap_out=remap_d)
+        assert rc_h == oracle.OK and rc_d == P.OK
+        assert (res_d.n_live, res_d.n_moved, res_d.old_num_blocks, res_d.new_num_blocks) == tuple(int(x) for x in res_h)
+        assert res_d.n_moved > 0
+        assert np.array_equal(remap_d.cpu().numpy(), remap_h)
+        for td, th in zip(tabs_d, tabs_h):
+            assert np.array_equal(td.cpu().numpy(), th)          # the oracle remapped its tables in place
+        assert np.array_equal(bitmap_ids(dev.live, 128), host.live_ids())
+        dev.sync_block_list()
+        assert_pools_equal(host, dev, range(cfg.num_layers), host.live_ids())
