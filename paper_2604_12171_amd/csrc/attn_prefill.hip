@@ -623,8 +623,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
       uint16_t *dst = (uint16_t *)p.out + row * D + 4 * qg;
 #pragma unroll
       for (int c = 0; c < ND; ++c) {
-        const uint32_t w0 = f32_to_bf16_rne(acc[c][nq][0] * inv) | ((uint32_t)f32_to_bf16_rne(acc[c][nq][1] * inv) << 16);
-        const uint32_t w1 = f32_to_bf16_rne(acc[c][nq][2] * inv) | ((uint32_t)f32_to_bf16_rne(acc[c][nq][3] * inv) << 16);
+        const uint32_t w0 = pack_bf16_rne(acc[c][nq][0] * inv, acc[c][nq][1] * inv);  // one conversion per pair
+        const uint32_t w1 = pack_bf16_rne(acc[c][nq][2] * inv, acc[c][nq][3] * inv);
         *(uint2 *)(dst + 16 * c) = make_uint2(w0, w1);
       }
     }
