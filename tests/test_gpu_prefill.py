@@ -164,6 +164,32 @@ def test_prefill_more_units_than_resident_workgroups_and_relaunch():
     assert P.pipelive_kv_read_state(dev).status == 0
 
 
+def test_clear_status_re_arms_the_prefill_work_counters():
+    """Counters left non-zero (as after a launch that was cut short) would make every workgroup stop after
+    its first unit; pipelive_kv_clear_status() zeroes them together with the status word."""
+    ctx = [300, 260]
+    cfg = pin.StageConfig("pf", 1, 8, 2, 64, 16, 2, 0, 0)
+    batch = _batch(cfg, ctx)
+    host, dev = make_pair(cfg, batch, SEED)
+    fill_pair(cfg, batch, SEED, host, dev)
+    qo = np.array([0, 300, 560], dtype=np.int32)
+    rng = np.random.default_rng(3)
+    q = pin.f32_to_bf16_bits(rng.standard_normal((560, 8, 64)).astype(np.float32))
+    q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
+    dev.state[20:28] = 77                                  # the two counters behind n_acc, t_applied, status
+    P.pipelive_kv_clear_status(dev)
+    out = torch.full((560, 8, 64), float("nan"), dtype=torch.float32, device="cuda")
+    P.pipelive_paged_attn_prefill(dev, 0, q_d, out, torch.from_numpy(batch.table).cuda(),
+                                  torch.from_numpy(batch.ctx_lens).cuda(), torch.from_numpy(qo).cuda(), 560)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    ref = host.attn_prefill(0, q, batch.table, batch.ctx_lens, qo, nthreads=8)
+    assert np.isfinite(got).all()
+    ma, rl = attn_errors(got, ref)
+    assert ma <= MAX_ABS and rl <= REL_L2, (ma, rl)
+    assert int(dev.state[20:28].sum()) == 0                # re-armed again by the launch itself
+
+
 def test_prefill_bad_table_entry_sets_status_and_spares_the_others():
     ctx, qlen = [100, 64, 200], [100, 10, 50]
     cfg = pin.StageConfig("pf", 1, 8, 2, 128, 16, 3, 0, 0)
