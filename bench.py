@@ -54,7 +54,7 @@ def parse_args():
     ap.add_argument("--shrink", type=float, default=0.20)
     ap.add_argument("--bulk-fraction", type=float, default=0.20, help="dirty fraction of the bulk patch round")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-layers", type=int, default=4, help="layers in the CPU oracle sample")
+    ap.add_argument("--cpu-layers", type=int, default=6, help="layers in the CPU oracle sample")
     ap.add_argument("--decode-only", action="store_true", help="profiling aid: steps run phase 1 only")
     return ap.parse_args()
 
