@@ -354,3 +354,75 @@ def geometric_fractions(first: float, last: float, rounds: int) -> list[float]:
         return [first]
     r = (last / first) ** (1.0 / (rounds - 1))
     return [first * r ** i for i in range(rounds)]
+
+
+# --------------------------------------------------------------------------
+# decode steps: the caller's block manager and the new tokens' K/V
+STREAM_NEWTOK = 7
+
+
+def new_token_bits(cfg: StageConfig, seed: int, step: int, layer: int):
+    """(k, v) uint16 [S][Hkv][D] each: K/V of the token every sequence appends in
+    decode step ``step`` at ``layer``."""
+    key = stream_key(seed, STREAM_NEWTOK)
+    n = cfg.num_seqs * cfg.num_kv_heads * cfg.head_dim
+    base = (step * cfg.num_layers + layer) * 2 * n
+    shape = (cfg.num_seqs, cfg.num_kv_heads, cfg.head_dim)
+    return bf16_normal(key, base, n).reshape(shape), bf16_normal(key, base + n, n).reshape(shape)
+
+
+class BlockManager:
+    """The serving engine's side of a decode batch (an *input* of the library, which is
+    told liveness and tables and never allocates ids itself): context lengths, block
+    table and the set of live ids, advanced one token per sequence per step.  A sequence
+    that fills its last block takes the lowest free id below the current pool size."""
+
+    def __init__(self, batch: Batch, capacity_blocks: int | None = None):
+        self.cfg = batch.cfg
+        self.num_blocks = int(batch.num_blocks)
+        cap = int(capacity_blocks or batch.num_blocks)
+        self.ctx = batch.ctx_lens.astype(np.int32).copy()
+        self.used = batch.used.astype(np.int32).copy()
+        self.table = batch.table.copy()
+        self.live = np.zeros(cap, dtype=bool)
+        self.live[batch.live_ids] = True
+
+    def set_num_blocks(self, n: int) -> None:
+        self.num_blocks = int(n)
+
+    def adopt(self, table: np.ndarray, live_ids) -> None:
+        """take over tables and liveness as a resize left them"""
+        self.table = table.copy()
+        self.live[:] = False
+        self.live[np.asarray(live_ids, dtype=np.int64)] = True
+
+    def live_ids(self) -> np.ndarray:
+        return np.nonzero(self.live)[0]
+
+    def step(self):
+        """Advance every sequence by one token.  Returns (positions int32 [S], the position
+        the new token is written at; new_entries [(seq, table column, block id)])."""
+        bs = self.cfg.block_tokens
+        pos = self.ctx.copy()
+        new_entries = []
+        free = None
+        for s in range(len(self.ctx)):
+            if int(pos[s]) == int(self.used[s]) * bs:        # last block full (or no block yet)
+                if int(self.used[s]) >= self.table.shape[1]:
+                    raise ValueError("block table row is full: draw the batch with stride_pad")
+                if free is None:
+                    free = iter(np.nonzero(~self.live[: self.num_blocks])[0])
+                try:
+                    b = int(next(free))
+                except StopIteration:
+                    raise ValueError("pool exhausted") from None
+                self.live[b] = True
+                self.table[s, self.used[s]] = b
+                new_entries.append((s, int(self.used[s]), b))
+                self.used[s] += 1
+        self.ctx = (self.ctx + 1).astype(np.int32)
+        return pos.astype(np.int32), new_entries
+
+    def last_block_ids(self) -> np.ndarray:
+        return np.asarray([int(self.table[s, self.used[s] - 1]) for s in range(len(self.ctx)) if self.used[s]],
+                          dtype=np.int64)
