@@ -17,7 +17,11 @@
  *    word in the region's device state is set; pipelive_kv_read_state
  *    returns it.
  *  - A handle is not re-entrant; distinct handles are independent.  Calls on
- *    one handle must be issued in stream order on one stream.
+ *    one handle must be issued in stream order on one stream, with one
+ *    exception that Sec. 6.1 needs (the sender drains while inference keeps
+ *    writing): pipelive_kv_patch_collect may run on a second stream beside
+ *    pipelive_kv_mark_dirty / pipelive_kv_append / pipelive_kv_append_chunk
+ *    calls that are issued, among themselves, in order on one stream.
  *
  * KV region layout (paper Sec. 5.1 "KV Cache Resizing", Sec. 5.2 "Layer
  * Stacking"): the cache is a *block list* of independently placed physical
@@ -78,7 +82,8 @@ typedef struct {
   int32_t block_tokens;    /* bs: 16, 32, 64 or 128 tokens per block */
   int32_t stack_k;         /* layers per physical block (Sec. 5.2); 1 = one pool per layer */
   int32_t dtype;           /* PIPELIVE_DTYPE_BF16 */
-  int32_t in_block_layout; /* PIPELIVE_LAYOUT_D8 */
+  int32_t in_block_layout; /* PIPELIVE_LAYOUT_D8, the only layout of the device library (the CPU
+                              oracle used by the tests also reads a plain row-major layout) */
   int32_t dirty_granularity; /* PIPELIVE_DIRTY_BLOCK: one dirty bit per block id;
                                 PIPELIVE_DIRTY_SLOT: one per token slot (unit id = block id * bs + slot),
                                 the paper's own granularity (Sec. 6.1) */
@@ -169,7 +174,9 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
  * total_q    HOST: q_offsets[num_seqs] (sizes the launch)
  * other arguments as for pipelive_paged_attn_decode; no workspace is needed.
  * A sequence with more queries than cached tokens sets the status word
- * (PIPELIVE_E_INVAL) and its rows are not written.  Asynchronous.
+ * (PIPELIVE_E_INVAL) and its rows are not written; so does a context longer
+ * than max_ctx (PIPELIVE_E_RANGE: unlike in decode it cannot be truncated, the
+ * query positions depend on it).  Asynchronous.
  * The kernel hands out its work through two counters in the region's
  * dev_state (zero between launches; the last workgroup re-arms them, so
  * replaying a captured launch is fine): two prefill calls on the same region
@@ -388,8 +395,11 @@ int64_t pipelive_patch_max_blocks(const pipelive_kv_t *kv, int32_t n_layers, siz
  *     header | int32 ids[max_blocks] | pad to 256 B | payload[r][i][blk]
  * where payload[r][i] is the verbatim K-then-V bytes of block ids[r] in layer
  * layers[i].  n_acc travels in the header (and restarts from 0) only when the
- * drain empties the bitmap.  A mark racing with the drain lands in this patch
- * or the next one, never nowhere.
+ * drain empties the bitmap.  A write that races with the drain (mark or append
+ * on another stream) lands in this patch or in the next one, never nowhere:
+ * writers store the slot, then set its bit, then count its tokens, and the
+ * drain takes the count before it takes the bits, so a patch never
+ * acknowledges tokens that neither it nor an earlier patch carries.
  *
  * layers         HOST int32 [n_layers] (region-local layer indices, patch order)
  * patch_buf      DEVICE, 256-B aligned, patch_capacity_bytes
@@ -402,17 +412,31 @@ int32_t pipelive_kv_patch_collect(pipelive_kv_t *src, const int32_t *layers, int
 
 /* apply: write every entry of the patch into block dst_block_map[id]
  * (identity when NULL) of layer dst_layers[i] of `dst`, then
- * T_applied += n_acc_tokens.  A header that does not match (magic, version,
- * n_layers, block_bytes) or an id outside dst sets the status word and skips
- * the entry.  Asynchronous.
+ * T_applied += n_acc_tokens.  The patch may come from another sender, so it is
+ * checked on the device before anything is written: a header that does not
+ * match the target (magic, version, n_layers, block_bytes, unit_tokens) or the
+ * buffer (n_blocks <= max_blocks, payload_offset = round_up(64 + 4 max_blocks,
+ * 256), payload inside patch_bytes) sets the status word to PIPELIVE_E_INVAL;
+ * a source id outside [0, map_entries) (without a map: outside dst), or one
+ * that the map sends outside dst, sets it to PIPELIVE_E_RANGE.  A refused
+ * patch is refused as a whole: no byte of dst changes and T_applied stays.
+ * Asynchronous.
  *
  * dst_layers     HOST int32 [n_layers]
- * dst_block_map  DEVICE int32 indexed by source *block* id, or NULL (a slot keeps
- *                its position inside the mapped block); source and target must
- *                have the same dirty granularity
+ * patch_bytes    HOST size of the buffer at patch_buf (what may be read)
+ * dst_block_map  DEVICE int32 [map_entries] indexed by source *block* id, or NULL
+ *                (a slot keeps its position inside the mapped block); source and
+ *                target must have the same dirty granularity
+ * map_entries    HOST number of entries of dst_block_map (ignored when it is NULL)
  */
 int32_t pipelive_kv_patch_apply(pipelive_kv_t *dst, const int32_t *dst_layers, int32_t n_layers,
-                                const void *patch_buf, const int32_t *dst_block_map, void *stream);
+                                const void *patch_buf, size_t patch_bytes,
+                                const int32_t *dst_block_map, int64_t map_entries, void *stream);
+
+/* T_applied of `dst` (Sec. 6.1: tokens acknowledged by the patches applied so
+ * far), read back with a blocking copy: the caller has synchronised the stream
+ * the applies were issued on.  Negative PIPELIVE_E_* on failure. */
+int64_t pipelive_kv_tokens_applied(const pipelive_kv_t *dst);
 
 /* Counters and status of a region; synchronises `stream`. */
 typedef struct {

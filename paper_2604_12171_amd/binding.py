@@ -31,7 +31,7 @@ EXPORTS = [
     "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_prefill", "pipelive_paged_attn_workspace_bytes",
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
-    "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state",
+    "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state", "pipelive_kv_tokens_applied",
     "pipelive_vmm_backing_bytes", "pipelive_vmm_pool_create", "pipelive_vmm_pool_destroy", "pipelive_vmm_pool_alloc",
     "pipelive_vmm_pool_free", "pipelive_vmm_pool_allocated", "pipelive_vmm_pool_base", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
     "pipelive_kv_clear_status", "pipelive_plan_reconfig", "pipelive_converged", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
@@ -82,7 +82,7 @@ def load(path: str | None = None):
     global _lib
     if _lib is not None:
         return _lib
-    path = path or os.environ.get("PIPELIVE_LIB") or _build.LIB  # PIPELIVE_LIB: development override
+    path = path or _build.LIB
     if not os.path.exists(path):
         _build.build_lib()
     L = C.CDLL(path)
@@ -125,7 +125,9 @@ def load(path: str | None = None):
     L.pipelive_kv_patch_collect.restype = i32
     L.pipelive_kv_patch_collect.argtypes = [vp, vp, i32, vp, sz, vp, vp]
     L.pipelive_kv_patch_apply.restype = i32
-    L.pipelive_kv_patch_apply.argtypes = [vp, vp, i32, vp, vp, vp]
+    L.pipelive_kv_patch_apply.argtypes = [vp, vp, i32, vp, sz, vp, i64, vp]
+    L.pipelive_kv_tokens_applied.restype = i64
+    L.pipelive_kv_tokens_applied.argtypes = [vp]
     L.pipelive_kv_read_state.restype = i32
     L.pipelive_kv_read_state.argtypes = [vp, C.POINTER(KVState), vp]
     L.pipelive_kv_clear_status.restype = i32
@@ -275,8 +277,17 @@ def pipelive_kv_patch_apply(dst: "KVRegion", dst_layers, patch_buf, dst_block_ma
     L = load()
     la = _i32_array(dst_layers)
     rc = L.pipelive_kv_patch_apply(dst.handle, la, len(dst_layers), _p(patch_buf),
-                                   _p(dst_block_map), _stream())
+                                   patch_buf.numel() * patch_buf.element_size(), _p(dst_block_map),
+                                   0 if dst_block_map is None else dst_block_map.numel(), _stream())
     return _check(rc) if check else rc
+
+
+def pipelive_kv_tokens_applied(dst: "KVRegion") -> int:
+    """T_applied; the caller has synchronised the stream of the applies."""
+    v = int(load().pipelive_kv_tokens_applied(dst.handle))
+    if v < 0:
+        raise PipeliveError(v)
+    return v
 
 
 def pipelive_patch_max_blocks(kv: "KVRegion", n_layers, capacity) -> int:

@@ -37,8 +37,7 @@ def stale() -> bool:
 def build_lib(force: bool = False, verbose: bool = False, out: str | None = None) -> str:
     if not force and not stale() and out is None:
         return LIB
-    extra = os.environ.get("PIPELIVE_EXTRA_HIPCC_FLAGS", "").split()
-    cmd = [_hipcc(), *FLAGS, *extra, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
+    cmd = [_hipcc(), *FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
            *[os.path.join(CSRC, s) for s in SOURCES], "-o", out or LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

@@ -165,9 +165,6 @@ size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_
   if (!attn_shape(kv, num_seqs, max_ctx, split_tokens, &sh)) return 0;
   const int G = kv->d.num_q_heads / kv->d.num_kv_heads;
   size_t bytes = (size_t)2 * sh.num_waves * attn_record_floats(G, kv->d.head_dim) * 4;
-#ifdef PIPELIVE_ATTN_TRACE
-  bytes += (size_t)sh.num_waves * 64;  // development builds: 8 timestamps per wave
-#endif
   return round_up(bytes, 256);
 }
 
@@ -417,13 +414,24 @@ int32_t pipelive_kv_patch_collect(pipelive_kv_t *src, const int32_t *layers, int
 }
 
 int32_t pipelive_kv_patch_apply(pipelive_kv_t *dst, const int32_t *dst_layers, int32_t n_layers,
-                                const void *patch_buf, const int32_t *dst_block_map, void *stream) {
+                                const void *patch_buf, size_t patch_bytes,
+                                const int32_t *dst_block_map, int64_t map_entries, void *stream) {
   if (!dst || !patch_buf || !aligned(patch_buf, 256)) return PIPELIVE_E_INVAL;
+  if (patch_bytes < 64 + 256 || (dst_block_map && map_entries < 0)) return PIPELIVE_E_INVAL;
   LayerList ll;
   int32_t rc = fill_layers(dst, dst_layers, n_layers, &ll);
   if (rc != PIPELIVE_OK) return rc;
-  HIP_TRY(launch_apply(dst, ll, (const uint8_t *)patch_buf, dst_block_map, (hipStream_t)stream));
+  HIP_TRY(launch_apply(dst, ll, (const uint8_t *)patch_buf, (uint64_t)patch_bytes, dst_block_map,
+                       map_entries, (hipStream_t)stream));
   return PIPELIVE_OK;
+}
+
+int64_t pipelive_kv_tokens_applied(const pipelive_kv_t *dst) {
+  if (!dst) return PIPELIVE_E_INVAL;
+  unsigned long long t = 0;
+  hipError_t e = hipMemcpy(&t, &dev_state(dst)->t_applied, sizeof t, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(e);
+  return (int64_t)t;
 }
 
 int32_t pipelive_kv_read_state(pipelive_kv_t *kv, pipelive_kv_state_t *out, void *stream) {

@@ -32,18 +32,6 @@ namespace pipelive {
 
 namespace {
 
-// Optional per-wave timestamps (development builds only): 8 slots per wave behind
-// the partial records in the workspace.
-#ifdef PIPELIVE_ATTN_TRACE
-#define TRACE_INIT() unsigned long long *trace_ = (unsigned long long *)(p.ws + 2 * (int64_t)p.num_waves * attn_record_floats(p.G, D)) + (int64_t)gw * 8
-#define TRACE(k) do { if (lane == 0) trace_[k] = wall_clock64(); } while (0)
-#define TRACE_ADD(k, v) do { if (lane == 0) trace_[k] += (v); } while (0)
-#else
-#define TRACE_INIT() do {} while (0)
-#define TRACE(k) do {} while (0)
-#define TRACE_ADD(k, v) do {} while (0)
-#endif
-
 
 __device__ __forceinline__ int tiles_of(int n, int max_ctx) {
   if (n > max_ctx) n = max_ctx;
@@ -148,8 +136,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
   const int r = lane & 15, qg = lane >> 4;
   const int G = p.G, Hkv = p.Hkv, S = p.num_seqs;
   if (gw >= p.num_waves) return;
-  TRACE_INIT();
-  TRACE(0);
 
   // ---- total number of tiles; rows of sequences without tokens are zeroed here
   int64_t carry = 0;
@@ -193,7 +179,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
   }
 
   const int64_t rec_sz = attn_record_floats(G, D);
-  TRACE(1);
 
   int64_t t = a;
   while (t < b) {
@@ -282,7 +267,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
         pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
         kc = kn;
         vc = vn;
-        if (i == 0) TRACE(2);
       }
       {  // last tile of the batch: nothing left to prefetch
         u32x4 ph, pl;
@@ -290,8 +274,6 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
         pv_accumulate<D>(vc, kc.nvalid[0], kc.nvalid[1], ph, pl, acc, qg);
       }
     }
-
-    TRACE(3);
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
     const int64_t row = (int64_t)s * p.Hq + (int64_t)g * G + r;
@@ -334,9 +316,7 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       }
     }
     t += cnt;
-    TRACE_ADD(5, 1);
   }
-  TRACE(4);
 }
 
 // Merge kernel: one wave per (sequence, KV head) pair that was cut by share

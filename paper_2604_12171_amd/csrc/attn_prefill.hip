@@ -109,7 +109,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         u.wb = (int)(nwb - 1 - rem % nwb);
         u.q0 = __builtin_amdgcn_readlane(sc.qa, k);
         u.qlen = __builtin_amdgcn_readlane(sc.ql, k);
-        u.n = min(__builtin_amdgcn_readlane(sc.cx, k), p.max_ctx);
+        // a context beyond max_ctx cannot be truncated here (the queries' positions hang on it): the
+        // unit is marked invalid (n = -1 < q_len) and skipped with PIPELIVE_E_RANGE
+        const int cx = __builtin_amdgcn_readlane(sc.cx, k);
+        u.n = cx > p.max_ctx ? -1 : cx;
       }
       carry += __builtin_amdgcn_readlane(inc, 63);
     }
@@ -290,8 +293,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   const int wb = __builtin_amdgcn_readfirstlane(cur.wb), q0 = __builtin_amdgcn_readfirstlane(cur.q0);
   const int qlen = __builtin_amdgcn_readfirstlane(cur.qlen), n = __builtin_amdgcn_readfirstlane(cur.n);
   cs = 0;  // start drawing the unit after this one
-  if (qlen > n) {  // more queries than cached tokens: flag and skip
-    if (tid == 0) atomicCAS(p.status, 0, PIPELIVE_E_INVAL);
+  if (qlen > n) {  // more queries than cached tokens, or a context beyond max_ctx (n = -1): flag and skip
+    if (tid == 0) atomicCAS(p.status, 0, n < 0 ? PIPELIVE_E_RANGE : PIPELIVE_E_INVAL);
   } else {
   // workgroup: the tiles its last query may see
   const int wg_tok0 = wb * WB;

@@ -15,7 +15,10 @@ struct DevState {
   int32_t status;                // sticky: first PIPELIVE_E_* seen on the device
   int32_t prefill_ticket;        // work distribution of the prefill kernel: both are zero whenever no
   int32_t prefill_finished;      // prefill launch of this region is running
-  int32_t pad_[9];
+  int32_t mark_blocks_done;      // workgroups of the running mark launch that have set their bits
+  unsigned long long n_acc_taken;  // drain: n_acc as taken before the first bitmap word was exchanged
+  int32_t apply_verdict;         // apply: PIPELIVE_OK or why the patch at hand is refused as a whole
+  int32_t pad_[5];
 };
 static_assert(sizeof(DevState) == 64, "DevState layout");
 constexpr size_t kSnapOffset = 256;
@@ -134,7 +137,8 @@ hipError_t launch_append_chunk(const pipelive_kv *kv, int32_t layer, const uint1
 hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_t *patch,
                           uint32_t max_blocks, uint64_t payload_offset, hipStream_t st);
 hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,
-                        const int32_t *dst_map, hipStream_t st);
+                        uint64_t patch_bytes, const int32_t *dst_map, int64_t map_entries,
+                        hipStream_t st);
 hipError_t launch_clear_status(const pipelive_kv *kv, hipStream_t st);
 
 int device_cu_count();

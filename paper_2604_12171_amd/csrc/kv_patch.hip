@@ -8,11 +8,15 @@
 //
 // append  : write one new token per sequence into its slot (K as 16-byte
 //           d-slices, V element-wise), mark the written unit, count tokens.
-// mark    : atomicOr of one bit per written unit; n_acc += n_tokens.
-// drain   : one workgroup swaps every bitmap word with zero (atomicExch, so a
-//           concurrent mark is either in this snapshot or stays for the next
-//           drain), prefix-sums the popcounts, writes the ascending id list
-//           and the header, and ORs back the bits beyond the patch capacity.
+// mark    : atomicOr of one bit per written unit; n_acc += n_tokens once every
+//           bit of the call is set.
+// drain   : takes n_acc, then one workgroup swaps every bitmap word with zero
+//           (atomicExch, so a concurrent mark is either in this snapshot or
+//           stays for the next drain), prefix-sums the popcounts, writes the
+//           ascending id list and the header, and ORs back the bits beyond the
+//           patch capacity.  Order of the two sides (writers: data, then bit,
+//           then count; drain: count, then bits): a patch never acknowledges a
+//           token whose slot it, or an earlier patch, does not carry.
 // gather  : persistent workgroups copy (block, layer) chunks into the payload;
 //           the number of blocks is read from the header on the device, so
 //           the host never waits for it.
@@ -26,10 +30,12 @@ namespace {
 
 typedef unsigned long long u64;
 
+constexpr int64_t kDrainOneWgWords = 4096;  // bitmaps up to this many words are drained by one workgroup
+constexpr int kDrainWordsPerLane = (int)(kDrainOneWgWords / kScanThreads);
+
 __global__ void mark_kernel(u64 *dirty, int64_t B, const int32_t *ids, int32_t n, u64 n_tokens,
                             DevState *st) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0 && n_tokens) atomicAdd(&st->n_acc, n_tokens);
   if (i < n) {
     const int32_t id = ids[i];
     if (id < 0 || id >= B) {
@@ -37,6 +43,19 @@ __global__ void mark_kernel(u64 *dirty, int64_t B, const int32_t *ids, int32_t n
     } else {
       atomicOr(&dirty[id >> 6], 1ull << (id & 63));
     }
+  }
+  if (n_tokens == 0) return;  // uniform over the launch
+  // the tokens are counted once every bit of this call is set: the last workgroup to get here adds them
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    bool last = gridDim.x == 1;
+    if (!last && atomicAdd(&st->mark_blocks_done, 1) == (int)gridDim.x - 1) {
+      atomicExch(&st->mark_blocks_done, 0);
+      __threadfence();
+      last = true;
+    }
+    if (last) atomicAdd(&st->n_acc, n_tokens);
   }
 }
 
@@ -46,14 +65,25 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
                                                              u64 block_bytes, u64 payload_offset,
                                                              uint32_t unit_tokens) {
   __shared__ uint32_t sh[17];
+  __shared__ u64 sh_acc;
   const int64_t nwords = (B + 63) / 64;
-  const int64_t per = (nwords + kScanThreads - 1) / kScanThreads;
+  const int64_t per = (nwords + kScanThreads - 1) / kScanThreads;  // <= kDrainOneWgWords / kScanThreads
   const int64_t w0 = (int64_t)threadIdx.x * per;
   const int64_t w1 = w0 + per < nwords ? w0 + per : nwords;
+  // n_acc is taken before the first word is exchanged (it goes back below if bits stay behind); the
+  // plain reads that tell which words need an exchange at all run beside it
+  if (threadIdx.x == 0) sh_acc = atomicExch(&st->n_acc, 0ull);
+  u64 seen[kDrainWordsPerLane];
+#pragma unroll
+  for (int k = 0; k < kDrainWordsPerLane; ++k) seen[k] = (w0 + k < w1) ? dirty[w0 + k] : 0ull;
+  __threadfence();
+  __syncthreads();
   uint32_t cnt = 0;
-  for (int64_t w = w0; w < w1; ++w) {
-    u64 v = dirty[w];
-    if (v) v = atomicExch(&dirty[w], 0ull);
+#pragma unroll
+  for (int k = 0; k < kDrainWordsPerLane; ++k) {
+    const int64_t w = w0 + k;
+    if (w >= w1) break;
+    const u64 v = seen[k] ? atomicExch(&dirty[w], 0ull) : 0ull;
     snap[w] = v;
     cnt += __popcll(v);
   }
@@ -81,7 +111,8 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
     h.n_layers = n_layers;
     h.block_bytes = block_bytes;
     h.more_pending = total > max_blocks ? 1u : 0u;
-    h.n_acc_tokens = h.more_pending ? 0ull : atomicExch(&st->n_acc, 0ull);
+    h.n_acc_tokens = h.more_pending ? 0ull : sh_acc;
+    if (h.more_pending && sh_acc) atomicAdd(&st->n_acc, sh_acc);
     h.payload_offset = payload_offset;
     h.max_blocks = max_blocks;
     h.unit_tokens = unit_tokens;
@@ -94,7 +125,9 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
 // words, e.g. slot granularity on a big pool): count per workgroup, scan the
 // workgroup counts, emit.  Same result as drain_kernel.
 constexpr int kDrainThreads = 256;
-constexpr int64_t kDrainOneWgWords = 4096;
+
+// first kernel of the large-bitmap drain: n_acc is taken before any word is exchanged
+__global__ void drain_begin_kernel(DevState *st) { st->n_acc_taken = atomicExch(&st->n_acc, 0ull); }
 
 __global__ __launch_bounds__(kDrainThreads) void drain_count_kernel(u64 *dirty, int64_t nwords, u64 *snap,
                                                                     uint32_t *wg_count) {
@@ -142,7 +175,10 @@ __global__ __launch_bounds__(kScanThreads) void drain_scan_kernel(uint32_t *wg_c
     h.n_layers = n_layers;
     h.block_bytes = block_bytes;
     h.more_pending = total > max_blocks ? 1u : 0u;
-    h.n_acc_tokens = h.more_pending ? 0ull : atomicExch(&st->n_acc, 0ull);
+    const u64 taken = st->n_acc_taken;  // by drain_begin_kernel, before the words were exchanged
+    st->n_acc_taken = 0;
+    h.n_acc_tokens = h.more_pending ? 0ull : taken;
+    if (h.more_pending && taken) atomicAdd(&st->n_acc, taken);
     h.payload_offset = payload_offset;
     h.max_blocks = max_blocks;
     h.unit_tokens = unit_tokens;
@@ -189,8 +225,54 @@ struct XferArgs {
   uint32_t Hkv, D, bs, unit_tokens;
   LayerList layers;
   const int32_t *dst_map;
+  int64_t map_entries;   // source block ids a patch may name: entries of dst_map, or num_blocks without a map
+  uint64_t patch_bytes;  // size of the buffer an incoming patch lies in
   DevState *st;
 };
+
+// The receiver's check of an incoming patch (it may come from another sender): header fields against the
+// target region and the buffer size, every id against the id space, every mapped id against the target.
+// One workgroup; the verdict goes to the region's device state and the scatter kernel behind it obeys
+// it: a patch that fails is refused as a whole (no byte written, T_applied unchanged, status set).
+__global__ __launch_bounds__(kScanThreads) void apply_check_kernel(XferArgs a, const uint8_t *patch) {
+  __shared__ int sh_bad;
+  const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
+  if (threadIdx.x == 0) sh_bad = 0;
+  __syncthreads();
+  int verdict = PIPELIVE_OK;
+  const uint64_t ids_end = 64 + 4 * (uint64_t)h->max_blocks;
+  if (a.patch_bytes < 64 || h->magic != PIPELIVE_PATCH_MAGIC || h->version != PIPELIVE_PATCH_VERSION ||
+      h->n_layers != (uint32_t)a.layers.n || h->block_bytes != a.blk_bytes || h->unit_tokens != a.unit_tokens) {
+    verdict = PIPELIVE_E_INVAL;
+  } else if (h->n_blocks > h->max_blocks || h->payload_offset != (ids_end + 255) / 256 * 256 ||
+             h->payload_offset > a.patch_bytes ||
+             (uint64_t)h->n_blocks * a.layers.n * a.blk_bytes > a.patch_bytes - h->payload_offset) {
+    verdict = PIPELIVE_E_INVAL;
+  } else {
+    const int32_t *ids = (const int32_t *)(patch + 64);
+    const int64_t upb = a.unit_tokens == 1 ? (int64_t)a.bs : 1;  // units per block
+    const uint32_t n = h->n_blocks;
+    bool bad = false;
+    for (uint32_t r = threadIdx.x; r < n; r += kScanThreads) {
+      const int64_t u = ids[r];
+      int64_t blk = u / upb;
+      if (u < 0 || blk >= a.map_entries) {
+        bad = true;
+      } else {
+        if (a.dst_map) blk = a.dst_map[blk];
+        if (blk < 0 || blk >= a.num_blocks) bad = true;
+      }
+    }
+    if (bad) sh_bad = 1;
+    __syncthreads();
+    if (sh_bad) verdict = PIPELIVE_E_RANGE;
+  }
+  if (threadIdx.x == 0) {
+    a.st->apply_verdict = verdict;
+    if (verdict != PIPELIVE_OK) atomicCAS(&a.st->status, 0, verdict);
+    else if (h->n_acc_tokens) atomicAdd(&a.st->t_applied, (u64)h->n_acc_tokens);
+  }
+}
 
 // payload[(r * n_layers + i) * blk] <- block ids[r] of layer layers[i]
 __global__ __launch_bounds__(kCopyThreads) void gather_kernel(XferArgs a, uint8_t *patch) {
@@ -217,18 +299,12 @@ __global__ __launch_bounds__(kCopyThreads) void gather_kernel(XferArgs a, uint8_
 
 // block dst_map[ids[r]] of layer layers[i] <- payload[(r * n_layers + i) * blk]
 __global__ __launch_bounds__(kCopyThreads) void scatter_kernel(XferArgs a, const uint8_t *patch) {
+  if (a.st->apply_verdict != PIPELIVE_OK) return;  // refused by apply_check_kernel: nothing is written
   const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
   const uint32_t nl = a.layers.n;
-  if (h->magic != PIPELIVE_PATCH_MAGIC || h->version != PIPELIVE_PATCH_VERSION ||
-      h->n_layers != nl || h->block_bytes != a.blk_bytes || h->unit_tokens != a.unit_tokens) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
-    return;
-  }
   const uint32_t n_blocks = h->n_blocks;
   const int32_t *ids = (const int32_t *)(patch + 64);
   const char *payload = (const char *)patch + h->payload_offset;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && h->n_acc_tokens)
-    atomicAdd(&a.st->t_applied, (u64)h->n_acc_tokens);
   const int64_t n_items = (int64_t)n_blocks * nl * a.subs_per_block;
   for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
     const uint32_t sub = (uint32_t)(item % a.subs_per_block);
@@ -236,12 +312,8 @@ __global__ __launch_bounds__(kCopyThreads) void scatter_kernel(XferArgs a, const
     const uint32_t i = (uint32_t)(e % nl);
     const int64_t r = e / nl;
     const int32_t layer = a.layers.layer[i];
-    int64_t id = ids[r];
+    int64_t id = ids[r];  // checked by apply_check_kernel, as is the mapped id
     if (a.dst_map) id = a.dst_map[id];
-    if (id < 0 || id >= a.num_blocks) {  // uniform over the workgroup
-      if (threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_RANGE);
-      continue;
-    }
     char *dst = (char *)a.block_list[(int64_t)(layer / a.stack_k) * a.capacity + id] +
                 (uint64_t)(layer % a.stack_k) * a.blk_bytes;
     const uint32_t off = sub * a.sub_bytes;
@@ -303,29 +375,19 @@ __global__ __launch_bounds__(kCopyThreads) void gather_slots_kernel(XferArgs a, 
 }
 
 __global__ __launch_bounds__(kCopyThreads) void scatter_slots_kernel(XferArgs a, const uint8_t *patch) {
+  if (a.st->apply_verdict != PIPELIVE_OK) return;  // refused by apply_check_kernel: nothing is written
   const pipelive_patch_hdr_t *h = (const pipelive_patch_hdr_t *)patch;
   const uint32_t nl = a.layers.n;
-  if (h->magic != PIPELIVE_PATCH_MAGIC || h->version != PIPELIVE_PATCH_VERSION ||
-      h->n_layers != nl || h->block_bytes != a.blk_bytes || h->unit_tokens != a.unit_tokens) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
-    return;
-  }
   const int32_t *ids = (const int32_t *)(patch + 64);
   const char *payload = (const char *)patch + h->payload_offset;
-  if (blockIdx.x == 0 && threadIdx.x == 0 && h->n_acc_tokens)
-    atomicAdd(&a.st->t_applied, (u64)h->n_acc_tokens);
   const int64_t n_items = (int64_t)h->n_blocks * nl;
   for (int64_t item = blockIdx.x; item < n_items; item += gridDim.x) {
     const uint32_t i = (uint32_t)(item % nl);
     const int64_t r = item / nl;
     const int32_t layer = a.layers.layer[i];
     const int32_t u = ids[r];
-    int64_t id = u / a.bs;
+    int64_t id = u / a.bs;  // checked by apply_check_kernel, as is the mapped id
     if (a.dst_map) id = a.dst_map[id];
-    if (id < 0 || id >= a.num_blocks) {  // uniform over the workgroup
-      if (threadIdx.x == 0) atomicCAS(&a.st->status, 0, PIPELIVE_E_RANGE);
-      continue;
-    }
     char *blk = (char *)a.block_list[(int64_t)(layer / a.stack_k) * a.capacity + id] +
                 (uint64_t)(layer % a.stack_k) * ((uint64_t)2 * a.Hkv * a.bs * a.D * 2);
     wg_copy_token<false>(blk, (char *)payload + (uint64_t)item * a.blk_bytes, u % a.bs, a.Hkv, a.D, a.bs);
@@ -377,7 +439,8 @@ __global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
   int s = -1, wi = 0;
   {
     int carry = 0;
-    for (int base = 0; base < S && s < 0; base += 64) {
+    // workgroup 0 looks at every sequence (it is the one that flags over-long chunks)
+    for (int base = 0; base < S && (s < 0 || blockIdx.x == 0); base += 64) {
       const bool in = base + lane < S;
       int nwin = 0;
       if (in) {
@@ -388,7 +451,7 @@ __global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
         if (ql > hi && blockIdx.x == 0 && tid < 64) atomicCAS(&a.st->status, 0, PIPELIVE_E_INVAL);
       }
       const int inc = wave_inclusive_scan(nwin, lane);
-      const uint64_t bal = __ballot(in && carry + inc > unit);
+      const uint64_t bal = s < 0 ? __ballot(in && carry + inc > unit) : 0ull;
       if (bal) {
         const int k = __ffsll((long long)bal) - 1;
         s = base + k;
@@ -477,15 +540,22 @@ __global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
       }
     }
   }
-  // ---- dirty marks and the token count, once per window (by the workgroup of KV head 0)
-  if (g == 0) {
-    if (a.mark && tid >= tt_lo && tid < tt_hi) {
-      const int j = 32 * w + tid;
-      const int32_t id = id_h[tid / sb];
-      const int64_t u = a.units_per_block > 1 ? (int64_t)id * bs + j % bs : id;
-      atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
-    }
-    if (a.count_tokens && tid == 0) atomicAdd(&a.st->n_acc, (unsigned long long)(tt_hi - tt_lo));
+  // ---- dirty marks after this head's bytes (every head's workgroup sets them: a drain that runs
+  // beside the chunk's writes must find the bit again after the last of them); the tokens are
+  // counted once per window, by the workgroup of KV head 0
+  if (!a.mark && !(a.count_tokens && g == 0)) return;
+  __threadfence();
+  __syncthreads();
+  if (a.mark && tid >= tt_lo && tid < tt_hi) {
+    const int j = 32 * w + tid;
+    const int32_t id = id_h[tid / sb];
+    const int64_t u = a.units_per_block > 1 ? (int64_t)id * bs + j % bs : id;
+    atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
+  }
+  if (a.count_tokens && g == 0) {
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) atomicAdd(&a.st->n_acc, (unsigned long long)(tt_hi - tt_lo));
   }
 }
 
@@ -512,12 +582,18 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
     *(u32x4 *)(blk + ((uint64_t)c * sb + tt) * 16) = *(const u32x4 *)(k + (uint64_t)c * 8);
   uint16_t *vblk = (uint16_t *)(blk + (uint64_t)a.Hkv * sb * a.D * 2);
   for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) vblk[(uint64_t)e * sb + tt] = v[e];
+  if (!a.mark && !a.count_tokens) return;
+  __threadfence();  // the slot's bytes, then its dirty bit, then the token count
+  __syncthreads();
   if (threadIdx.x == 0) {
     if (a.mark) {
       const int64_t u = a.units_per_block > 1 ? (int64_t)id * a.bs + t : id;
       atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
     }
-    if (a.count_tokens) atomicAdd(&a.st->n_acc, 1ull);
+    if (a.count_tokens) {
+      __threadfence();
+      atomicAdd(&a.st->n_acc, 1ull);
+    }
   }
 }
 
@@ -543,6 +619,8 @@ XferArgs make_xfer(const pipelive_kv *kv, const LayerList &layers, const int32_t
   a.subs_per_block = (a.blk_bytes + a.sub_bytes - 1) / a.sub_bytes;
   a.layers = layers;
   a.dst_map = dst_map;
+  a.map_entries = kv->d.num_blocks;
+  a.patch_bytes = 0;
   a.st = dev_state(kv);
   return a;
 }
@@ -631,6 +709,8 @@ hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_
   } else {
     const int64_t n_wg = (nwords + kDrainThreads - 1) / kDrainThreads;
     uint32_t *wg_count = (uint32_t *)(snap_words(kv) + nwords);  // behind the snapshot words
+    hipLaunchKernelGGL(drain_begin_kernel, dim3(1), dim3(1), 0, st, dev_state(kv));
+    if ((e = hipGetLastError()) != hipSuccess) return e;
     hipLaunchKernelGGL(drain_count_kernel, dim3((unsigned)n_wg), dim3(kDrainThreads), 0, st,
                        (u64 *)kv->d.dirty_bitmap, nwords, snap_words(kv), wg_count);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -653,8 +733,14 @@ hipError_t launch_collect(const pipelive_kv *kv, const LayerList &layers, uint8_
 }
 
 hipError_t launch_apply(const pipelive_kv *kv, const LayerList &layers, const uint8_t *patch,
-                        const int32_t *dst_map, hipStream_t st) {
+                        uint64_t patch_bytes, const int32_t *dst_map, int64_t map_entries,
+                        hipStream_t st) {
   XferArgs a = make_xfer(kv, layers, dst_map);
+  a.patch_bytes = patch_bytes;
+  a.map_entries = dst_map ? map_entries : kv->d.num_blocks;
+  hipLaunchKernelGGL(apply_check_kernel, dim3(1), dim3(kScanThreads), 0, st, a, patch);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const int grid = device_cu_count() * copy_wgs_per_cu();
   if (kv->units_per_block > 1)
     hipLaunchKernelGGL(scatter_slots_kernel, dim3(grid), dim3(kCopyThreads), 0, st, a, patch);

@@ -55,6 +55,30 @@ def _oracle_pair(cfg, batch, capacity, layer, s, epoch=0):
     return host.attn_decode(0, q, tab, np.array([n], dtype=np.int32))[0]
 
 
+def _oracle_pair_after_appends(cfg, batch0, capacity, layer, s, steps):
+    """Oracle attention of one (layer, sequence) after `steps` decode steps: the original tokens are
+    regenerated from the ids they were written at (content follows a block through every resize), the
+    appended ones come from the new-token generator and are placed by the oracle's own append."""
+    n0, u0 = int(batch0.ctx_lens[s]), int(batch0.used[s])
+    n = n0 + steps
+    u = (n + cfg.block_tokens - 1) // cfg.block_tokens
+    host = oracle.HostKV(1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, u,
+                         layout=cfg.layout, arenas=2, fill_bits=pin.BF16_NAN)
+    for j in range(u0):
+        bits = pin.kv_block_bits(cfg, SEED, capacity, 0, layer, int(batch0.table[s, j]))
+        valid = min(cfg.block_tokens, n0 - j * cfg.block_tokens)
+        if valid < cfg.block_tokens:
+            bits = bits.copy()
+            bits[pin.token_slot_mask(cfg.layout, cfg.num_kv_heads, cfg.block_tokens, cfg.head_dim, valid)] = pin.BF16_NAN
+        host.block(0, j)[:] = bits
+    tab = np.arange(u, dtype=np.int32)[None, :]
+    for k in range(steps):
+        kk, vv = pin.new_token_bits(cfg, SEED, k, layer)
+        assert host.append(0, kk[s:s + 1], vv[s:s + 1], tab, np.array([n0 + k], dtype=np.int32), mark=False) == oracle.OK
+    q = pin.q_bits(cfg, SEED, layer)[s:s + 1]
+    return host.attn_decode(0, q, tab, np.array([n], dtype=np.int32))[0]
+
+
 def _sample_pairs(cfg, n_pairs, salt):
     h = pin.hash_u64(pin.stream_key(SEED, pin.STREAM_MISC) ^ salt, np.arange(2 * n_pairs, dtype=np.uint64))
     layers = (h[:n_pairs] % np.uint64(cfg.num_layers)).astype(int)
@@ -65,10 +89,10 @@ def _sample_pairs(cfg, n_pairs, salt):
 class Stage:
     """Device region + tensors of one workload."""
 
-    def __init__(self, cfg, B, capacity=None, arenas=4, stack_k=1, backing="arena"):
+    def __init__(self, cfg, B, capacity=None, arenas=4, stack_k=1, backing="arena", stride_pad=0):
         self.cfg, self.B = cfg, B
         self.cap = capacity or B
-        self.batch = pin.draw_batch(cfg, SEED, num_blocks=B)
+        self.batch = pin.draw_batch(cfg, SEED, num_blocks=B, stride_pad=stride_pad)
         self.region = P.KVRegion(cfg.num_layers, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
                                  cfg.block_tokens, B, capacity_blocks=self.cap, arenas=arenas, stack_k=stack_k,
                                  backing=backing)
@@ -77,7 +101,7 @@ class Stage:
         self.ctx = torch.from_numpy(self.batch.ctx_lens).cuda()
         self.used = torch.from_numpy(self.batch.used).cuda()
         self.max_ctx = int(self.batch.ctx_lens.max())
-        self.ws = self.region.attn_workspace(cfg.num_seqs, self.max_ctx, 0)
+        self.ws = self.region.attn_workspace(cfg.num_seqs, self.max_ctx + 64 * stride_pad, 0)
 
     def decode(self, layer):
         cfg = self.cfg
@@ -86,6 +110,26 @@ class Stage:
         P.pipelive_paged_attn_decode(self.region, layer, q, out, self.table, self.ctx, max_ctx=self.max_ctx,
                                      workspace=self.ws)
         return out
+
+    def append_step(self, bm, step, count_layer=0, mark=True):
+        """One decode step's writes: the block manager hands out the slots (new blocks = lowest free id),
+        every layer appends its token.  Returns the positions written."""
+        cfg = self.cfg
+        pos, new_entries = bm.step()
+        for s, col, b in new_entries:
+            self.table[s, col] = b
+        if new_entries:
+            self.region.set_live(bm.live_ids())
+            self.used.copy_(torch.from_numpy(bm.used))
+        pos_d = torch.from_numpy(pos).cuda()
+        for l in range(cfg.num_layers):
+            kk, vv = pin.new_token_bits(cfg, SEED, step, l)
+            P.pipelive_kv_append(self.region, l, torch.from_numpy(kk.view(np.int16)).cuda().view(torch.bfloat16),
+                                 torch.from_numpy(vv.view(np.int16)).cuda().view(torch.bfloat16), self.table, pos_d,
+                                 mark=mark, count_tokens=(l == count_layer))
+        self.ctx.copy_(torch.from_numpy(bm.ctx))
+        self.max_ctx = int(bm.ctx.max())
+        return pos, new_entries
 
     def check_attention(self, n_pairs, salt):
         """GPU vs oracle on sampled (layer, sequence) pairs; returns the GPU outputs per layer.
@@ -112,7 +156,7 @@ class Stage:
         return self.region.read_blocks(layer, ids).view(torch.int64).sum(dim=1)
 
 
-def _resize_and_check(st, B_new, tag):
+def _resize_and_check(st, B_new, tag, check_content=True):
     """Shrink on both sides, compare all state, check that content followed the blocks."""
     cfg, batch = st.cfg, st.batch
     so = _state_oracle(st.B, st.cap)
@@ -121,7 +165,7 @@ def _resize_and_check(st, B_new, tag):
     so.set_live(live_before)
     table_h = st.table.cpu().numpy().copy()
     sums_before = {l: st.block_sums(l, live_before) for l in (0, cfg.num_layers - 1)}
-    rc_h, remap_h, res_h = so.resize(B_new, [table_h], [batch.used])
+    rc_h, remap_h, res_h = so.resize(B_new, [table_h], [st.used.cpu().numpy()])
     remap_d = torch.full((st.region.num_blocks,), -9, dtype=torch.int32, device="cuda")
     rc_d, res_d = P.pipelive_kv_resize(st.region, B_new, [st.table], [st.used], remap_out=remap_d)
     assert rc_h == oracle.OK and rc_d == P.OK, (rc_h, rc_d)
@@ -135,7 +179,7 @@ def _resize_and_check(st, B_new, tag):
     for l, before in sums_before.items():            # every live block, on the device
         assert torch.equal(st.block_sums(l, new_ids), before)
     moved = live_before[remap_h[live_before] != live_before]
-    for b in moved[:: max(1, len(moved) // 6)][:6]:     # sampled moved blocks against numpy regeneration
+    for b in moved[:: max(1, len(moved) // 6)][:6] if check_content else []:     # sampled moved blocks against numpy regeneration
         l = int(b) % cfg.num_layers
         got = st.region.block(l, int(remap_h[b])).cpu().numpy().view(np.uint16)
         exp = pin.kv_block_bits(cfg, SEED, st.cap, 0, l, int(b))   # content is keyed by the id it was written at
@@ -174,8 +218,11 @@ def test_stage8b_decode_in_bench_configuration():
     torch.cuda.empty_cache()
 
 
-def test_resize8b_shrink_grow_shrink_with_decode():
-    """Workload 3: tight pool, the stage grows 16 -> 20 layers so every pool shrinks by 20 %."""
+def test_resize8b_shrink_decode_with_appends_grow_shrink():
+    """Workload 3: tight pool, the stage grows 16 -> 20 layers so every pool shrinks by 20 % while the batch
+    keeps decoding: decode -> shrink -> decode (bit-identical) -> 16 decode steps that append a token per
+    sequence in every layer (new blocks take the lowest free id) -> grow back -> decode -> shrink again ->
+    decode; attention after the appends against the oracle on 64 sampled (layer, sequence) pairs."""
     cfg = pin.CONFIGS["resize8b"]
     ctx = pin.draw_ctx_lens(cfg, SEED)
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
@@ -183,24 +230,50 @@ def test_resize8b_shrink_grow_shrink_with_decode():
     B_new = int(B * 16 // 20)
     assert n_live <= B_new
     log(f"resize8b: B {B} -> {B_new}, live {n_live}")
-    st = Stage(cfg, B)
+    st = Stage(cfg, B, stride_pad=2)
+    batch0 = st.batch
     before = st.check_attention(64, salt=3)
     table_h, _ = _resize_and_check(st, B_new, "shrink")
     after = {l: st.decode(l).cpu().numpy() for l in before}
     for l in before:                                   # attention unchanged bit for bit
         assert np.array_equal(before[l].view(np.uint32), after[l].view(np.uint32)), l
-    # grow back (nothing moves), then shrink again (nothing left in the tail)
+    # 16 decode steps on the shrunken pool
+    bm = pin.BlockManager(batch0, B)
+    bm.set_num_blocks(B_new)
+    bm.adopt(table_h, bitmap_ids(st.region.live, st.cap))
+    steps, n_new = 16, 0
+    for k in range(steps):
+        _, new_entries = st.append_step(bm, k, count_layer=-1, mark=False)
+        assert all(b < B_new for _, _, b in new_entries)
+        n_new += len(new_entries)
+    torch.cuda.synchronize()
+    assert n_new > 0 and np.array_equal(st.table.cpu().numpy(), bm.table)
+    assert np.array_equal(bitmap_ids(st.region.live, st.cap), bm.live_ids())
+    log(f"  {steps} decode steps appended {steps * cfg.num_seqs} tokens per layer into {n_new} new blocks")
+    # grow back (nothing moves): decode against the oracle on sampled pairs
     rc, res = P.pipelive_kv_resize(st.region, B, [st.table], [st.used])
     assert rc == P.OK and res.n_moved == 0 and st.region.num_blocks == B
-    rc, res = P.pipelive_kv_resize(st.region, B_new, [st.table], [st.used])
-    assert rc == P.OK and res.n_moved == 0
-    again = {l: st.decode(l).cpu().numpy() for l in before}
-    for l in before:
-        assert np.array_equal(before[l].view(np.uint32), again[l].view(np.uint32)), l
+    pairs = _sample_pairs(cfg, 64, 33)
+    outs = {l: st.decode(l).cpu().numpy() for l in sorted({l for l, _ in pairs})}
+    oracle.lib()
+    with ThreadPoolExecutor(max_workers=12) as ex:
+        refs = list(ex.map(lambda ls: _oracle_pair_after_appends(cfg, batch0, st.cap, ls[0], ls[1], steps), pairs))
+    worst = (0.0, 0.0)
+    for (l, s), ref in zip(pairs, refs):
+        ma, rl = attn_errors(outs[l][s], ref)
+        assert ma <= MAX_ABS and rl <= REL_L2, (l, s, ma, rl)
+        worst = (max(worst[0], ma), max(worst[1], rl))
+    log(f"  attention after the appends: {len(pairs)} pairs, worst max_abs {worst[0]:.2e} rel_l2 {worst[1]:.2e}")
+    # shrink again: tables, remap and bitmaps against the oracle, attention bit-identical
+    table_h2, _ = _resize_and_check(st, B_new, "second shrink", check_content=False)
+    again = {l: st.decode(l).cpu().numpy() for l in outs}
+    for l in outs:
+        assert np.array_equal(outs[l].view(np.uint32), again[l].view(np.uint32)), l
     # infeasible request: nothing changes
     rc, res = P.pipelive_kv_resize(st.region, n_live - 1, [st.table], [st.used])
     assert rc == P.E_INFEASIBLE and st.region.num_blocks == B_new
-    assert np.array_equal(st.table.cpu().numpy(), table_h)
+    assert np.array_equal(st.table.cpu().numpy(), table_h2)
+    assert P.pipelive_kv_read_state(st.region).status == 0
     del st
     torch.cuda.empty_cache()
 
@@ -213,8 +286,10 @@ def test_stage70b_incremental_patching_six_rounds():
     B = int(math.ceil(1.25 * n_live))
     L = cfg.num_layers
     log(f"stage70b: source and target {B} blocks/layer x {L} layers ({B * L * cfg.blk_bytes / 2**30:.1f} GiB each), free {_free_gb():.0f} GiB")
-    st = Stage(cfg, B)
-    st.check_attention(24, salt=4)
+    st = Stage(cfg, B, stride_pad=2)
+    st.check_attention(64, salt=4)
+    bm = pin.BlockManager(st.batch, B)
+    touched = set()
     tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3)
     so = _state_oracle(B)
     so_t = _state_oracle(B)
@@ -232,15 +307,23 @@ def test_stage70b_incremental_patching_six_rounds():
         if rnd == 0:
             ids, ntok = live, 0
         else:
-            ids = pin.draw_dirty_ids(st.batch, SEED, rnd, fr[rnd - 1])
+            # the decode step between two rounds: every sequence appends one token in every layer (fused
+            # dirty mark; layer 0 counts the tokens); the state oracle mirrors bits and count with its own append
+            pos, _ = st.append_step(bm, rnd - 1)
+            so.set_live(bm.live_ids())
+            z = np.zeros((cfg.num_seqs, 1, 8), dtype=np.uint16)
+            assert so.append(0, z, z, bm.table, pos, mark=True, count_tokens=True) == oracle.OK
+            touched |= set(bm.last_block_ids().tolist())
             ntok = cfg.num_seqs
-            for l in (0, 7, L - 1):                     # the writes of this round (sampled layers get new content)
+            # ... and a seeded sample of live blocks is rewritten (sampled layers get new content) and marked
+            ids = pin.draw_dirty_ids(st.batch, SEED, rnd, fr[rnd - 1], include_last=False)
+            for l in (0, 7, L - 1):
                 data = pin.kv_blocks_bits_torch(cfg, SEED, B, rnd, l, ids[:256], "cuda")
                 st.region.write_blocks(l, ids[:256], data)
         sched += ntok
         ids32 = torch.from_numpy(np.asarray(ids, dtype=np.int32)).cuda()
-        assert so.mark_dirty(ids, ntok) == oracle.OK
-        P.pipelive_kv_mark_dirty(st.region, ids32, ntok)
+        assert so.mark_dirty(ids, 0) == oracle.OK
+        P.pipelive_kv_mark_dirty(st.region, ids32, 0)
         drains = 0
         while True:
             # the state oracle drains with the same id capacity
@@ -270,7 +353,8 @@ def test_stage70b_incremental_patching_six_rounds():
             drains += 1
             if not g["more_pending"]:
                 break
-        log(f"  round {rnd}: {len(ids)} dirty blocks in {drains} drain(s), n_acc {ntok}")
+        log(f"  round {rnd}: {len(ids)} sampled/live blocks marked (+ appends), {drains} drain(s), n_acc {ntok}")
+    live = bm.live_ids()
     assert applied_ids == set(live.tolist())
     stt = P.pipelive_kv_read_state(tgt)
     assert stt.t_applied == sched == so_t.t_applied and stt.status == 0
@@ -281,7 +365,7 @@ def test_stage70b_incremental_patching_six_rounds():
         l = int(b) % L
         got = tgt.block(l, int(b)).cpu().numpy().view(np.uint16)
         exp = pin.kv_block_bits(cfg, SEED, B, 0, l, int(b))
-        assert np.array_equal(got, exp) or _tail_ok(cfg, st.batch, b, got, exp) or l in (0, 7, L - 1)
+        assert np.array_equal(got, exp) or _tail_ok(cfg, st.batch, b, got, exp) or l in (0, 7, L - 1) or int(b) in touched
     del st, tgt, patch
     torch.cuda.empty_cache()
 
@@ -296,7 +380,7 @@ def test_longctx8b_split_decode_resize_and_final_patch():
     assert n_live <= B_new
     log(f"longctx8b: B {B} -> {B_new}, live {n_live}, free {_free_gb():.0f} GiB")
     st = Stage(cfg, B)
-    before = st.check_attention(8, salt=5)
+    before = st.check_attention(64, salt=5)
     table_h, remap_h = _resize_and_check(st, B_new, "shrink 25 %")
     after = {l: st.decode(l).cpu().numpy() for l in before}
     for l in before:

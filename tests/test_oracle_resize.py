@@ -225,3 +225,47 @@ def test_max_blocks_closed_form():
     assert oracle.max_blocks(100.0, 1.0, 2, 10.0, 4.0) == 10
     assert oracle.max_blocks(100.0, 1.0, 2, 10.0, 4.1) == 9
     assert oracle.max_blocks(10.0, 1.0, 2, 10.0, 4.0) == 0
+
+
+@pytest.mark.parametrize("gran", [0, 1])
+def test_grow_clears_stale_bits_of_the_new_ids_and_moves_nothing(gran):
+    """Sec. 5.1: expansion appends newly allocated blocks to the block list.  The ids in [B, B_new) start
+    out neither live nor dirty whatever their bits held before (an earlier shrink leaves them behind);
+    ids below B, tables and every byte of the pool stay as they are; remap is the identity on live ids."""
+    bs, B, cap, B_new = 4, 10, 24, 19
+    kv = oracle.HostKV(2, 2, 1, 8, bs, B, capacity_blocks=cap, arenas=3, dirty_gran=gran)
+    _fill_blocks(kv, seed=3)
+    before = _snapshot(kv)
+    live = [0, 3, 4, 9]
+    kv.set_live(live)
+    upb = bs if gran else 1
+    # stale bits: live bits at ids 10, 13, 18 (to be cleared), 19 and 23 (beyond B_new: not the call's business)
+    for b in (10, 13, 18, 19, 23):
+        kv.live[b >> 3] |= 1 << (b & 7)
+    stale_dirty = [10 * upb, 13 * upb + upb - 1, 18 * upb + upb - 1, 19 * upb, 23 * upb + upb - 1]
+    for u in stale_dirty:
+        kv.dirty[u >> 3] |= 1 << (u & 7)
+    table = np.array([[0, 3, 9], [4, pin.TABLE_FILL, pin.TABLE_FILL]], dtype=np.int32)
+    used = np.array([3, 1], dtype=np.int32)
+    t0 = table.copy()
+    rc, remap, res = kv.resize(B_new, [table], [used])
+    assert rc == oracle.OK and kv.num_blocks == B_new
+    assert res.tolist() == [4, 0, B, B_new]
+    assert kv.live_ids().tolist() == live                      # ids [B, B_new) are not live
+    all_live = np.nonzero(np.unpackbits(kv.live, bitorder="little")[:cap])[0].tolist()
+    assert all_live == live + [19, 23]                         # bits at ids >= B_new were not touched
+    all_dirty = np.nonzero(np.unpackbits(kv.dirty, bitorder="little")[:cap * upb])[0].tolist()
+    assert all_dirty == [19 * upb, 23 * upb + upb - 1]         # dirty bits of the new ids are gone, too
+    assert np.array_equal(table, t0)
+    assert remap[:B].tolist() == [b if b in live else -1 for b in range(B)]
+    for l in range(2):
+        for b in range(cap):
+            assert np.array_equal(kv.block(l, b), before[l][b])
+    # a grow is refused while a dirty bit below B is pending, and then changes nothing
+    kv2 = oracle.HostKV(1, 2, 1, 8, bs, B, capacity_blocks=cap, dirty_gran=gran)
+    kv2.set_live(live)
+    kv2.live[13 >> 3] |= 1 << (13 & 7)
+    assert kv2.mark_dirty([3 * upb], 1) == oracle.OK
+    rc, _, _ = kv2.resize(B_new, [], [])
+    assert rc == oracle.E_BUSY and kv2.num_blocks == B
+    assert (kv2.live[13 >> 3] >> (13 & 7)) & 1
