@@ -156,6 +156,27 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
 size_t pipelive_paged_attn_workspace_bytes(const pipelive_kv_t *kv, int32_t num_seqs,
                                            int32_t max_ctx, int32_t split_tokens);
 
+/* For callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * operation, kernels and result (bit for bit) as pipelive_paged_attn_decode,
+ * with the partial records kept in a scratch buffer that is built into the
+ * library (a __device__ array of pipelive_noalloc_scratch_bytes() = 16 MiB
+ * which every GPU the library runs on holds until the process ends).  The call
+ * allocates nothing and frees nothing.  A launch shape whose records do not fit
+ * (pipelive_paged_attn_workspace_bytes(...) above that size; only explicit
+ * split_tokens on very large batches get there) returns PIPELIVE_E_NOSPACE and
+ * launches nothing.  All calls on one GPU share the one buffer, whatever the
+ * region or stream: calls that may overlap in time on a GPU race on it and must
+ * use pipelive_paged_attn_decode with workspaces of their own instead.  Nothing
+ * in the buffer has to survive between calls and nothing has to be zero at the
+ * start of one.  Other arguments and errors as for pipelive_paged_attn_decode. */
+int32_t pipelive_paged_attn_decode_noalloc(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                           int32_t out_dtype, const int32_t *block_table,
+                                           int32_t table_stride, const int32_t *ctx_lens,
+                                           int32_t num_seqs, int32_t max_ctx, float scale,
+                                           int32_t split_tokens, void *stream);
+size_t pipelive_noalloc_scratch_bytes(void);
+
 /* Chunked-prefill attention of ONE layer over the same KV layout (Sec. 2 "LLM
  * Inference": the prompt's tokens are processed in parallel; compute-bound).
  * The new chunk's K/V is already in the cache (pipelive_kv_append_chunk or

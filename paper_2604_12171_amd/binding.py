@@ -29,6 +29,7 @@ PATCH_MAGIC = 0x564B4C50
 EXPORTS = [
     "pipelive_bitmap_bytes", "pipelive_kv_dirty_units", "pipelive_kv_append", "pipelive_kv_append_chunk", "pipelive_kv_state_bytes", "pipelive_kv_create", "pipelive_kv_destroy",
     "pipelive_kv_num_blocks", "pipelive_paged_attn_decode", "pipelive_paged_attn_prefill", "pipelive_paged_attn_workspace_bytes",
+    "pipelive_paged_attn_decode_noalloc", "pipelive_noalloc_scratch_bytes",
     "pipelive_kv_resize", "pipelive_kv_resize_workspace_bytes",
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state", "pipelive_kv_tokens_applied",
@@ -106,6 +107,10 @@ def load(path: str | None = None):
     L.pipelive_paged_attn_decode.restype = i32
     L.pipelive_paged_attn_decode.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, i32, i32, C.c_float,
                                              i32, vp, sz, vp]
+    L.pipelive_paged_attn_decode_noalloc.restype = i32
+    L.pipelive_paged_attn_decode_noalloc.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, i32, i32, C.c_float, i32, vp]
+    L.pipelive_noalloc_scratch_bytes.restype = sz
+    L.pipelive_noalloc_scratch_bytes.argtypes = []
     L.pipelive_paged_attn_prefill.restype = i32
     L.pipelive_paged_attn_prefill.argtypes = [vp, i32, vp, vp, i32, vp, i32, vp, vp, i32, i32, i32,
                                               C.c_float, vp]
@@ -207,6 +212,17 @@ def pipelive_paged_attn_decode(kv: "KVRegion", layer, q, out, block_table, ctx_l
                                       _p(block_table), stride, _p(ctx_lens), S, int(max_ctx),
                                       float(scale), int(split_tokens), _p(workspace),
                                       workspace.numel() * workspace.element_size(), _stream())
+    return _check(rc) if check else rc
+
+
+def pipelive_paged_attn_decode_noalloc(kv: "KVRegion", layer, q, out, block_table, ctx_lens, max_ctx=0,
+                                       scale=0.0, split_tokens=0, check=True):
+    """As pipelive_paged_attn_decode, on the library's built-in scratch buffer (the call allocates nothing)."""
+    out_dtype = OUT_F32 if out.dtype == torch.float32 else OUT_BF16
+    rc = load().pipelive_paged_attn_decode_noalloc(kv.handle, int(layer), _p(q), _p(out), out_dtype,
+                                                   _p(block_table), int(block_table.shape[1]), _p(ctx_lens),
+                                                   int(ctx_lens.shape[0]), int(max_ctx), float(scale),
+                                                   int(split_tokens), _stream())
     return _check(rc) if check else rc
 
 

@@ -5,6 +5,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "internal.h"
@@ -19,6 +20,33 @@ inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 int g_cu_count = 0;
+
+// Scratch memory built into the library for pipelive_paged_attn_decode_noalloc: the partial records
+// of a decode launch.  Every device the library runs on holds its own copy of the array at its own
+// address; host code never uses the array's name for that memory, only the address looked up below.
+constexpr size_t kNoallocScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+__device__ __align__(256) unsigned char scratch[kNoallocScratchBytes];
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up once per device)
+int32_t noalloc_scratch(void **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return pipelive::hip_fail(e);
+  if (dev < 0 || dev >= kMaxDevices) return PIPELIVE_E_INVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return pipelive::hip_fail(e);
+    if (!ptr) return PIPELIVE_E_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return PIPELIVE_OK;
+}
 
 }  // namespace
 
@@ -209,6 +237,27 @@ int32_t pipelive_paged_attn_decode(const pipelive_kv_t *kv, int32_t layer, const
   if (p.Hq > 65535) return PIPELIVE_E_INVAL;
   HIP_TRY(launch_attn_decode(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));
   return PIPELIVE_OK;
+}
+
+size_t pipelive_noalloc_scratch_bytes(void) { return kNoallocScratchBytes; }
+
+int32_t pipelive_paged_attn_decode_noalloc(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
+                                           int32_t out_dtype, const int32_t *block_table,
+                                           int32_t table_stride, const int32_t *ctx_lens,
+                                           int32_t num_seqs, int32_t max_ctx, float scale,
+                                           int32_t split_tokens, void *stream) {
+  if (!kv || table_stride <= 0) return PIPELIVE_E_INVAL;
+  if (num_seqs > 0) {
+    const size_t need = pipelive_paged_attn_workspace_bytes(kv, num_seqs, effective_max_ctx(kv, table_stride, max_ctx),
+                                                            split_tokens);
+    if (need == 0) return PIPELIVE_E_INVAL;
+    if (need > kNoallocScratchBytes) return PIPELIVE_E_NOSPACE;  // this launch shape needs a caller's workspace
+  }
+  void *ptr = nullptr;
+  const int32_t rc = noalloc_scratch(&ptr);
+  if (rc != PIPELIVE_OK) return rc;
+  return pipelive_paged_attn_decode(kv, layer, q, out, out_dtype, block_table, table_stride, ctx_lens, num_seqs,
+                                    max_ctx, scale, split_tokens, ptr, kNoallocScratchBytes, stream);
 }
 
 int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, const void *q, void *out,
