@@ -66,7 +66,15 @@ def parse_args():
                     help="profiling aid: the steps run decode attention only, followed by one plain copy of known size")
     ap.add_argument("--prefill-only", action="store_true",
                     help="profiling aid: run only the prefill cases of the 8B stage's heads")
+    ap.add_argument("--prefill-case", default="both", choices=["both", "prompt512", "chunk512_of_4096"],
+                    help="with --prefill-only: which of the two cases")
     ap.add_argument("--decode-iters", type=int, default=50)
+    ap.add_argument("--placement-probe", action="store_true",
+                    help="measure the copy paths of the 70B stage on four successive allocations of the same pools "
+                         "(same kernels, same ids: only the physical placement of the buffers differs)")
+    ap.add_argument("--core-only", action="store_true",
+                    help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
+                         "stacked pool, 4-layer rounds, sparse pool)")
     return ap.parse_args()
 
 
@@ -389,7 +397,7 @@ def run_stage70b(c: Ctx, headline: bool):
     # ---- the same decay with 4 migrating layers (secondary)
     lay4 = list(range(L - 4, L))
     r4 = []
-    for r in (1, 6):
+    for r in (() if args.core_only else (1, 6)):
         sample = pin.draw_dirty_ids(st.batch, c.seed, r, fr[r - 1], include_last=True)
         ids32 = torch.from_numpy(sample.astype(np.int32)).cuda()
         out = time_patch_round(c, st.region, tgt, ids32, 0, lay4, patch, None, 5, cfg.blk_bytes, B)
@@ -581,6 +589,8 @@ def run_stage8b(c: Ctx, headline: bool):
     del bulk_patch
     if P.pipelive_kv_read_state(target).status != 0 or not st.status_ok():
         raise RuntimeError("device status word set during the 8B-stage legs")
+    if args.core_only:
+        return res, head, None
 
     # ---- steady-state decode at slot granularity (the paper's own unit): every layer appends one token
     # per sequence, the written slots are drained and applied
@@ -629,6 +639,8 @@ def run_prefill(c: Ctx, cfg):
     np, torch, pin, P = c.np, c.torch, c.pin, c.P
     pres = {}
     for tag, Sp, ctxp, qlp in (("prompt512", 64, 512, 512), ("chunk512_of_4096", 16, 4096, 512)):
+        if c.args.prefill_only and c.args.prefill_case not in ("both", tag):
+            continue
         pcfg = pin.StageConfig(tag, 1, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
                                Sp, ctxp, ctxp)
         pb = pin.draw_batch(pcfg, c.seed, pool_factor=1.25)
@@ -877,6 +889,7 @@ def run_longctx8b(c: Ctx, headline: bool):
     dmap = dmap.cuda()
     patch = torch.empty(patch_capacity(len(live), L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
     live32 = torch.from_numpy(live.astype(np.int32)).cuda()
+    applied0 = P.pipelive_kv_read_state(tgt).t_applied
     res["round0"] = time_patch_round(c, st.region, tgt, live32, 0, layers, patch, dmap, 2, cfg.blk_bytes, B_new)
     ids = pin.draw_dirty_ids(bt, c.seed, 1, 0.02)
     ids32 = torch.from_numpy(ids.astype(np.int32)).cuda()
@@ -887,10 +900,39 @@ def run_longctx8b(c: Ctx, headline: bool):
     for l in (0, L - 1):
         if not torch.equal(tgt.read_blocks(l, compact), st.region.read_blocks(l, live)):
             raise RuntimeError(f"longctx8b: target differs from source in layer {l}")
-    if P.pipelive_kv_read_state(tgt).t_applied != S or not st.status_ok():
+    if P.pipelive_kv_read_state(tgt).t_applied - applied0 != S or not st.status_ok():
         raise RuntimeError("longctx8b: counters or status wrong")
     del tgt, patch
     return res, head, None
+
+
+def run_placement_probe(c: Ctx):
+    """The 70B stage's shrink and a 20 % patch round on four successive allocations of the same pools."""
+    np, torch, pin, P = c.np, c.torch, c.pin, c.P
+    cfg = pin.CONFIGS["stage70b"]
+    L = cfg.num_layers
+    ctx = pin.draw_ctx_lens(cfg, c.seed)
+    n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
+    B = int(math.ceil(1.25 * n_live))
+    out = []
+    keep = []
+    for k in range(4):
+        st = Stage(c, cfg, B, arenas=4, poison=False)
+        tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3)
+        ids = torch.from_numpy(pin.draw_dirty_ids(st.batch, c.seed, 1, 0.20).astype(np.int32)).cuda()
+        patch = torch.empty(patch_capacity(ids.numel(), L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+        r = time_patch_round(c, st.region, tgt, ids, 0, list(range(L)), patch, None, 5, cfg.blk_bytes, B)
+        z = st.time_shrink(int(B * 0.8), 5)
+        out.append({"allocation": k, "collect_frac_of_peak": r["collect_frac_of_peak"],
+                    "apply_frac_of_peak": r["apply_frac_of_peak"], "resize_frac_of_peak": z["frac_of_peak"],
+                    "source_arena0_addr": hex(st.region.arenas[0].data_ptr()), "patch_addr": hex(patch.data_ptr())})
+        log(f"[placement] {out[-1]}")
+        del st, tgt, patch
+        if k == 1:   # the third and fourth round get their memory while a 40 GiB hole is held elsewhere
+            c.free_all()
+            keep.append(torch.empty(40 << 30, dtype=torch.uint8, device="cuda"))
+        c.free_all()
+    return out
 
 
 def run_tiny(c: Ctx):
@@ -1094,6 +1136,9 @@ def main():
     if args.prefill_only:
         print(json.dumps({"prefill": run_prefill(c, c.pin.CONFIGS["stage8b"])}), flush=True)
         return
+    if args.placement_probe:
+        print(json.dumps({"placement_probe": run_placement_probe(c)}), flush=True)
+        return
     runners = {"stage70b": run_stage70b, "stage8b": run_stage8b, "resize8b": run_resize8b, "longctx8b": run_longctx8b}
     headline_name = HEADLINE if args.config == "all" else args.config
     if headline_name not in runners:
@@ -1140,7 +1185,7 @@ def main():
                 configs[name] = r
                 del s2
             c.free_all()
-            if name == "resize8b":
+            if name == "resize8b" and not args.core_only:
                 configs[name]["sparse_pool"] = run_resize8b_sparse(c)
                 c.free_all()
             log(f"[{name}] done in {time.time() - t0:.1f}s")
