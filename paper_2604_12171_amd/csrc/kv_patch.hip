@@ -30,6 +30,26 @@ namespace {
 
 typedef unsigned long long u64;
 
+// Ordering between a writer (slot bytes, then dirty bit, then token count) and a drain that runs beside it
+// on another stream (count, then bits, then bytes).  Every access that takes part is a device-scope
+// operation that bypasses the per-XCD L2 (atomics, write-through stores, device-scope loads), so "earlier"
+// only has to mean "acknowledged before the next one is issued": order_point() waits for the wave's
+// outstanding memory operations and nothing else.  It writes back or invalidates no cache, unlike a
+// device-scope fence, which costs several microseconds per launch on this chip.
+__device__ __forceinline__ void order_point() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // keeps the compiler from moving accesses across
+  __builtin_amdgcn_s_waitcnt(0x0F70);                     // s_waitcnt vmcnt(0): stores and atomics acknowledged
+}
+
+template <typename T>
+__device__ __forceinline__ void store_through(T *p, T v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ u64 load_through(const u64 *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 constexpr int64_t kDrainOneWgWords = 4096;  // bitmaps up to this many words are drained by one workgroup
 constexpr int kDrainWordsPerLane = (int)(kDrainOneWgWords / kScanThreads);
 
@@ -46,13 +66,12 @@ __global__ void mark_kernel(u64 *dirty, int64_t B, const int32_t *ids, int32_t n
   }
   if (n_tokens == 0) return;  // uniform over the launch
   // the tokens are counted once every bit of this call is set: the last workgroup to get here adds them
-  __threadfence();
+  order_point();
   __syncthreads();
   if (threadIdx.x == 0) {
     bool last = gridDim.x == 1;
     if (!last && atomicAdd(&st->mark_blocks_done, 1) == (int)gridDim.x - 1) {
       atomicExch(&st->mark_blocks_done, 0);
-      __threadfence();
       last = true;
     }
     if (last) atomicAdd(&st->n_acc, n_tokens);
@@ -70,14 +89,14 @@ __global__ __launch_bounds__(kScanThreads) void drain_kernel(u64 *dirty, int64_t
   const int64_t per = (nwords + kScanThreads - 1) / kScanThreads;  // <= kDrainOneWgWords / kScanThreads
   const int64_t w0 = (int64_t)threadIdx.x * per;
   const int64_t w1 = w0 + per < nwords ? w0 + per : nwords;
-  // n_acc is taken before the first word is exchanged (it goes back below if bits stay behind); the
-  // plain reads that tell which words need an exchange at all run beside it
+  // n_acc is taken before the first word is looked at (it goes back below if bits stay behind): a count
+  // taken here belongs to bits that were set before it, and the reads below come after it
   if (threadIdx.x == 0) sh_acc = atomicExch(&st->n_acc, 0ull);
+  __syncthreads();
+  // which words need an exchange at all
   u64 seen[kDrainWordsPerLane];
 #pragma unroll
-  for (int k = 0; k < kDrainWordsPerLane; ++k) seen[k] = (w0 + k < w1) ? dirty[w0 + k] : 0ull;
-  __threadfence();
-  __syncthreads();
+  for (int k = 0; k < kDrainWordsPerLane; ++k) seen[k] = (w0 + k < w1) ? load_through(&dirty[w0 + k]) : 0ull;
   uint32_t cnt = 0;
 #pragma unroll
   for (int k = 0; k < kDrainWordsPerLane; ++k) {
@@ -135,7 +154,7 @@ __global__ __launch_bounds__(kDrainThreads) void drain_count_kernel(u64 *dirty, 
   const int64_t w = (int64_t)blockIdx.x * kDrainThreads + threadIdx.x;
   u64 v = 0;
   if (w < nwords) {
-    v = dirty[w];
+    v = load_through(&dirty[w]);
     if (v) v = atomicExch(&dirty[w], 0ull);
     snap[w] = v;
   }
@@ -544,7 +563,7 @@ __global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
   // beside the chunk's writes must find the bit again after the last of them); the tokens are
   // counted once per window, by the workgroup of KV head 0
   if (!a.mark && !(a.count_tokens && g == 0)) return;
-  __threadfence();
+  __threadfence();  // this window's bytes are plain 16-byte stores: written back before the bits are set
   __syncthreads();
   if (a.mark && tid >= tt_lo && tid < tt_hi) {
     const int j = 32 * w + tid;
@@ -553,7 +572,7 @@ __global__ __launch_bounds__(256) void append_chunk_kernel(AppendChunkArgs a) {
     atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
   }
   if (a.count_tokens && g == 0) {
-    __threadfence();
+    order_point();
     __syncthreads();
     if (tid == 0) atomicAdd(&a.st->n_acc, (unsigned long long)(tt_hi - tt_lo));
   }
@@ -578,12 +597,20 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
   char *blk = token_sub_block((char *)a.block_list[id] + a.layer_off, t, a.Hkv, a.D, a.bs, sb, tt);
   const uint32_t n_el = a.Hkv * a.D;
   const uint16_t *k = a.k_new + (int64_t)s * n_el, *v = a.v_new + (int64_t)s * n_el;
-  for (uint32_t c = threadIdx.x; c < n_el / 8; c += blockDim.x)
-    *(u32x4 *)(blk + ((uint64_t)c * sb + tt) * 16) = *(const u32x4 *)(k + (uint64_t)c * 8);
+  // the slot's bytes go through to memory (a drain on another stream may read them as soon as it finds
+  // the bit), then the dirty bit, then the token count
+  for (uint32_t c = threadIdx.x; c < n_el / 8; c += blockDim.x) {
+    const u32x4 piece = *(const u32x4 *)(k + (uint64_t)c * 8);
+    uint32_t *dst = (uint32_t *)(blk + ((uint64_t)c * sb + tt) * 16);
+    store_through(dst + 0, piece.x);
+    store_through(dst + 1, piece.y);
+    store_through(dst + 2, piece.z);
+    store_through(dst + 3, piece.w);
+  }
   uint16_t *vblk = (uint16_t *)(blk + (uint64_t)a.Hkv * sb * a.D * 2);
-  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) vblk[(uint64_t)e * sb + tt] = v[e];
+  for (uint32_t e = threadIdx.x; e < n_el; e += blockDim.x) store_through(&vblk[(uint64_t)e * sb + tt], v[e]);
   if (!a.mark && !a.count_tokens) return;
-  __threadfence();  // the slot's bytes, then its dirty bit, then the token count
+  order_point();
   __syncthreads();
   if (threadIdx.x == 0) {
     if (a.mark) {
@@ -591,7 +618,7 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
       atomicOr(&a.dirty[u >> 6], 1ull << (u & 63));
     }
     if (a.count_tokens) {
-      __threadfence();
+      order_point();
       atomicAdd(&a.st->n_acc, 1ull);
     }
   }
