@@ -158,6 +158,7 @@ static bool attn_shape(const pipelive_kv_t *kv, int32_t num_seqs, int32_t max_ct
                        int32_t split_tokens, AttnShape *out) {
   if (split_tokens < 0 || split_tokens % 32) return false;
   const int64_t upper = (int64_t)num_seqs * kv->d.num_kv_heads * ((max_ctx + 31) / 32);
+  if (upper >= (1ll << 31)) return false;  // the kernels' share arithmetic is 32-bit
   if (split_tokens == 0) {
     // equal shares over exactly the waves the device keeps resident
     // One wave per SIMD: measured on MI355X, 768-1024 waves with one 16 KiB tile in

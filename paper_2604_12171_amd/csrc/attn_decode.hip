@@ -115,17 +115,21 @@ __device__ __forceinline__ void pv_accumulate(VRegs<D> &t, int nv0, int nv1, u32
 // Fixed mode (tiles_per_wave > 0): wave w owns [w*Q, (w+1)*Q).
 // Balanced mode: total = nw*Qf + rem; the first `rem` waves own Qf+1 tiles, the
 // others Qf, so no wave carries more than one tile above the mean.
+// The host admits only launches whose tile count is below 2^31, so every
+// quotient here is a 32-bit division (a 64-bit one is a long emulated sequence
+// that sits in front of a wave's first load).
+__device__ __forceinline__ uint32_t div32(int64_t a, int64_t b) { return (uint32_t)a / (uint32_t)b; }
 __device__ __forceinline__ int64_t share_start(const AttnParams &p, int64_t total, int64_t w) {
   if (p.tiles_per_wave > 0) return w * p.tiles_per_wave;
-  const int64_t qf = total / p.num_waves, rem = total % p.num_waves;
+  const int64_t qf = div32(total, p.num_waves), rem = total - qf * p.num_waves;
   return w * qf + (w < rem ? w : rem);
 }
 __device__ __forceinline__ int64_t share_wave(const AttnParams &p, int64_t total, int64_t t) {
-  if (p.tiles_per_wave > 0) return t / p.tiles_per_wave;
-  const int64_t qf = total / p.num_waves, rem = total % p.num_waves;
+  if (p.tiles_per_wave > 0) return div32(t, p.tiles_per_wave);
+  const int64_t qf = div32(total, p.num_waves), rem = total - qf * p.num_waves;
   const int64_t big = rem * (qf + 1);
-  if (t < big) return t / (qf + 1);
-  return rem + (t - big) / qf;  // qf > 0 here because t < total
+  if (t < big) return div32(t, qf + 1);
+  return rem + div32(t - big, qf);  // qf > 0 here because t < total
 }
 
 template <int D, int BS>
@@ -192,8 +196,8 @@ __global__ __launch_bounds__(256, 2) void attn_decode_kernel(AttnParams p) {
       ++s;
       continue;
     }
-    const int g = (int)(rem / ts);
-    const int j0 = (int)(rem % ts);
+    const int g = (int)div32(rem, ts);
+    const int j0 = (int)(rem - (int64_t)g * ts);
     const int cnt = (int)min((int64_t)(ts - j0), b - t);  // tiles of this pair inside the share
     const int64_t T0 = t - j0;                            // flat start of the pair
 

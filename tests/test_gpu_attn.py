@@ -145,11 +145,12 @@ def test_argument_errors():
         P.KVRegion(2, 4, 2, 96, 16, 8)                     # head_dim not supported
 
 
-def test_many_sequences_multi_chunk_scan_and_all_empty():
-    """More than 64 sequences (the wave-wide prefix sums run in several chunks),
-    many of them empty or a single token; then a batch with no tokens at all."""
+@pytest.mark.parametrize("n_seqs", [200, 300])
+def test_many_sequences_multi_chunk_scan_and_all_empty(n_seqs):
+    """More than 64 sequences (the wave-wide prefix sums run in several chunks), many of them empty or a
+    single token; then a batch with no tokens at all."""
     rng = np.random.default_rng(5)
-    ctx = rng.integers(0, 90, 200).astype(np.int32)
+    ctx = rng.integers(0, 90, n_seqs).astype(np.int32)
     ctx[::7] = 0
     ctx[3::11] = 1
     ctx[150] = 1500
