@@ -458,6 +458,10 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
       for (int T = 0; T < 2; ++T) sc[nq][T] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // the wave asks for issue priority while it feeds the MFMA pipe (QK products here, PV products
+    // below) and gives it back for the softmax: the CU's other workgroup then fills the gaps with its
+    // vector instructions instead of delaying these (measured: 2-3 % on long chunks)
+    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
     for (int c = 0; c < NC; ++c)
 #pragma unroll
@@ -475,6 +479,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     u32x4 vreg[ND];
 #pragma unroll
     for (int c = 0; c < ND; ++c) vreg[c] = *(lds_u4)(st + vlane + 16 * c * St::VROW);
+    __builtin_amdgcn_s_setprio(0);
     __builtin_amdgcn_sched_barrier(0);
 
     // raw scores; the scale (positive) is applied inside the exponent: exp2(s * c - m)
@@ -552,6 +557,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     }
     // the denominators: sum over the tile's tokens of the same bf16 weights, as one more row of V^T
     // that holds ones (every row of the 16 x 16 result is that sum: no cross-lane reduction later)
+    __builtin_amdgcn_s_setprio(2);
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
       lacc[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, as_bf16x8(ph[nq]), lacc[nq], 0, 0, 0);
@@ -574,6 +580,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
             acc[c + u][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vreg[c + u]), as_bf16x8(pl[nq]), acc[c + u][nq], 0, 0, 0);
       }
     }
+    __builtin_amdgcn_s_setprio(0);
   };
 
   // ---- the tile loop: copies are issued two tiles ahead of the arithmetic and need to have landed
