@@ -346,7 +346,7 @@ def run_stage70b(c: Ctx, headline: bool):
         res["resize"] = st.time_shrink(B_new, 10)
 
     # ---- the migration: round 0 (pre-copy of every live block, in as many drains as the buffer sized for
-    # round 1 needs), then six rounds; between rounds every sequence decodes one token (append in every
+    # patch round 1 needs), then six patch rounds; between rounds every sequence decodes one token (append in every
     # layer, fused dirty mark) and a seeded sample of live blocks is rewritten-and-marked
     bm = pin.BlockManager(st.batch, B)
     t_applied0 = P.pipelive_kv_read_state(tgt).t_applied
@@ -371,7 +371,7 @@ def run_stage70b(c: Ctx, headline: bool):
     pay0 = blocks0 * L * cfg.blk_bytes
     res["round0"] = {"dirty_blocks": blocks0, "drains": drains, "payload_bytes": int(pay0), "ms": round(ms0, 3),
                      "collect_plus_apply_GBps": round(4 * pay0 / ms0 / 1e6, 1),
-                     "note": "buffer sized for round 1, so the pre-copy takes several clipped drains with a host "
+                     "note": "buffer sized for patch round 1, so the pre-copy takes several clipped drains with a host "
                              "read of the header between them"}
     rounds, sched = [], 0
     for r in range(1, 7):

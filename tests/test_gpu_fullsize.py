@@ -297,7 +297,7 @@ def test_stage70b_incremental_patching_six_rounds():
     layers = list(range(L))
     fr = pin.geometric_fractions(0.20, 0.01, 6)
     n_r1 = len(pin.draw_dirty_ids(st.batch, SEED, 1, fr[0]))
-    cap_small = 64 + 256 + (n_r1 + 8) * (4 + L * cfg.blk_bytes)     # sized for round 1; round 0 is clipped
+    cap_small = 64 + 256 + (n_r1 + 8) * (4 + L * cfg.blk_bytes)     # sized for patch round 1; the pre-copy round is clipped
     patch = torch.empty(cap_small, dtype=torch.uint8, device="cuda")
     patch_h = np.zeros(64 + 256 + (n_r1 + 8) * (4 + so.blk_bytes) + 8 * B, dtype=np.uint8)
     max_blocks = P.pipelive_patch_max_blocks(st.region, L, cap_small)
