@@ -72,6 +72,10 @@ def parse_args():
     ap.add_argument("--placement-probe", action="store_true",
                     help="measure the copy paths of the 70B stage on four successive allocations of the same pools "
                          "(same kernels, same ids: only the physical placement of the buffers differs)")
+    ap.add_argument("--placement-warmup-gib", type=int, default=64,
+                    help="allocate and free this many GiB before the first pool is allocated (0: not). The "
+                         "first 48-64 GiB a process is handed lie where in-pool copies run at 0.63 instead of "
+                         "0.78 of the HBM peak on this part; a server would do the same once at start-up")
     ap.add_argument("--core-only", action="store_true",
                     help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
                          "stacked pool, 4-layer rounds, sparse pool)")
@@ -1143,6 +1147,16 @@ def main():
     if args.placement_probe:
         print(json.dumps({"placement_probe": run_placement_probe(c)}), flush=True)
         return
+    placement = {"warmup_GiB": 0}
+    if args.placement_warmup_gib > 0:
+        free_b = torch.cuda.mem_get_info()[0]
+        gib = min(args.placement_warmup_gib, int(free_b * 0.9) >> 30)
+        if gib > 0:
+            ballast = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
+            del ballast
+            c.free_all()
+            placement = {"warmup_GiB": gib,
+                         "note": "one allocation of this size made and freed before the first pool is allocated"}
     runners = {"stage70b": run_stage70b, "stage8b": run_stage8b, "resize8b": run_resize8b, "longctx8b": run_longctx8b}
     headline_name = HEADLINE if args.config == "all" else args.config
     if headline_name not in runners:
@@ -1165,7 +1179,7 @@ def main():
         "config": {"workload": _wl_name(cfg), "pool_blocks_per_layer": res["pool_blocks_per_layer"],
                    "pool_GiB": res["pool_GiB"], "live_blocks_per_layer": res["live_blocks_per_layer"],
                    "tokens": res["tokens"], "split_tokens": int(args.split_tokens), "device": c.dev_name,
-                   "decode_only": bool(args.decode_only)},
+                   "decode_only": bool(args.decode_only), "placement": placement},
         "step_bytes": head["step_bytes"],
         "roofline": head["roofline"],
     }
