@@ -72,6 +72,12 @@ def parse_args():
     ap.add_argument("--placement-probe", action="store_true",
                     help="measure the copy paths of the 70B stage on four successive allocations of the same pools "
                          "(same kernels, same ids: only the physical placement of the buffers differs)")
+    ap.add_argument("--patch-ways", type=int, default=3,
+                    help="runs of physical memory the patch buffers of a workload are striped over, backed "
+                         "before, between and behind its pools (0: the buffers are torch allocations)")
+    ap.add_argument("--patch-parts", default="0,2",
+                    help="how many of those runs are backed before the source pool, between the pools (the rest "
+                         "behind the target pool)")
     ap.add_argument("--placement-warmup-gib", type=int, default=64,
                     help="allocate and free this many GiB before the first pool is allocated (0: not). The "
                          "first 48-64 GiB a process is handed lie where in-pool copies run at 0.63 instead of "
@@ -132,6 +138,45 @@ class Ctx:
         import gc
         gc.collect()
         self.torch.cuda.empty_cache()
+
+    # ---- Placement of a workload's patch buffers: one striped range (64 MiB pieces over three runs of
+    # physical memory) whose runs are backed before the source pool, between the pools and behind the
+    # target pool, so that a gather's writes and a scatter's reads are spread over the device memory
+    # instead of falling into one place (--patch-ways 0: torch's own allocations).
+    prange = None
+    _parts = 0
+
+    def patch_range_open(self, nbytes):
+        self.patch_range_close()
+        ways = int(getattr(self.args, "patch_ways", 0))
+        if ways > 0:
+            self.prange = self.P.StripedRange(int(nbytes) + (64 << 20), ways=ways, back_now=False)
+            self._parts = 0
+            self._sched = [int(x) for x in str(getattr(self.args, "patch_parts", "0,2")).split(",")]
+            self.patch_range_next()
+
+    def patch_range_next(self, rest=False):
+        """back the runs of the next point of the schedule (all remaining ones with rest=True)"""
+        if self.prange is None:
+            return
+        n = self.prange.ways if rest or not self._sched else self._sched.pop(0)
+        while n > 0 and self._parts < self.prange.ways:
+            self.prange.back(self._parts)
+            self._parts += 1
+            n -= 1
+
+    def patch_range_close(self):
+        if self.prange is not None:
+            self.sync()
+            self.prange.close()
+            self.prange = None
+
+    def big_u8(self, n):
+        if self.prange is not None:
+            self.patch_range_next(rest=True)
+            if self.prange.room() >= n:
+                return self.prange.empty(n, self.torch.uint8)
+        return self.torch.empty(n, dtype=self.torch.uint8, device="cuda")
 
 
 class Stage:
@@ -327,6 +372,8 @@ def run_stage70b(c: Ctx, headline: bool):
     ctx = pin.draw_ctx_lens(cfg, c.seed)
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(1.25 * n_live))
+    if not args.decode_only:
+        c.patch_range_open(patch_capacity(int(0.21 * n_live) + S + 8, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4, stride_pad=2)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -335,11 +382,12 @@ def run_stage70b(c: Ctx, headline: bool):
         head = timed_steps(c, st, None, None, None, None, decode_only=True)
         res["decode"] = head["decode"]
         return res, head, st
+    c.patch_range_next()
     tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3)
     fr = pin.geometric_fractions(0.20, 0.01, 6)
     n_r1 = len(pin.draw_dirty_ids(st.batch, c.seed, 1, fr[0]))
     layers = list(range(L))
-    patch = torch.empty(patch_capacity(n_r1 + S + 8, L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+    patch = c.big_u8(patch_capacity(n_r1 + S + 8, L, cfg.blk_bytes))
     B_new = int(B * 0.8)
     if headline:
         head = timed_steps(c, st, tgt, layers, patch, B_new)
@@ -541,6 +589,8 @@ def run_stage8b(c: Ctx, headline: bool):
         extra = n_live * L * cfg.blk_bytes * (1.0 + bulk_fraction + 0.05) + (8 << 30)
         B = min(B, int((free - extra) // (L * cfg.blk_bytes)))
     B = max(B, int(math.ceil(n_live * 1.3)))
+    if not args.decode_only:
+        c.patch_range_open(patch_capacity(int((bulk_fraction + 0.01) * n_live) + 2 * S, L, cfg.blk_bytes) + (64 << 20))
     st = Stage(c, cfg, B, arenas=4)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "free_after_weights_GiB": round(free / 2**30, 1), "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -550,13 +600,14 @@ def run_stage8b(c: Ctx, headline: bool):
         return res, head, st
     Lm = 4
     mig_layers = list(range(L - Lm, L))
+    c.patch_range_next()
     target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2)
     dst_map = torch.full((B,), -1, dtype=torch.int32)
     dst_map[torch.from_numpy(st.batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
     dst_map = dst_map.cuda()
     B_new = int(B * 0.8)
     head = None
-    patch = torch.empty(patch_capacity(S, Lm, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+    patch = c.big_u8(patch_capacity(S, Lm, cfg.blk_bytes))
     if headline:
         head = timed_steps(c, st, target, mig_layers, patch, B_new, dst_map=dst_map)
         res.update({k: head[k] for k in ("decode", "patch", "resize", "switch_us")})
@@ -572,7 +623,7 @@ def run_stage8b(c: Ctx, headline: bool):
     # ---- bulk patch round: 20 % of the live blocks, all layers
     bulk_ids = torch.from_numpy(pin.draw_dirty_ids(st.batch, c.seed, 1, bulk_fraction).astype(np.int32)).cuda()
     all_layers = list(range(L))
-    bulk_patch = torch.empty(patch_capacity(bulk_ids.numel(), L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+    bulk_patch = c.big_u8(patch_capacity(bulk_ids.numel(), L, cfg.blk_bytes))
     res["patch_bulk"] = time_patch_round(c, st.region, target, bulk_ids, 0, all_layers, bulk_patch, dst_map, 10,
                                          cfg.blk_bytes, B)
     # context: what torch's own device-to-device copy reaches inside that buffer (read + write counted)
@@ -780,6 +831,8 @@ def run_resize8b(c: Ctx, headline: bool):
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(n_live / 0.75))
     B_new = B * 16 // 20
+    if headline and not args.decode_only:
+        c.patch_range_open(patch_capacity(S, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4, stride_pad=2)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens, "pool_reading": "tight pool: B = ceil(n_live / 0.75)"}
@@ -789,8 +842,9 @@ def run_resize8b(c: Ctx, headline: bool):
         res["decode"] = head["decode"]
         return res, head, st
     if headline:
+        c.patch_range_next()
         tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=2)
-        patch = torch.empty(patch_capacity(S, L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+        patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         head = timed_steps(c, st, tgt, list(range(L)), patch, B_new)
         maybe_cpu_baseline(c, st, head)
         del tgt, patch
@@ -859,6 +913,8 @@ def run_longctx8b(c: Ctx, headline: bool):
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(n_live / 0.70))
     B_new = int(B * 0.75)
+    if not args.decode_only:
+        c.patch_range_open(patch_capacity(n_live + S, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -868,9 +924,10 @@ def run_longctx8b(c: Ctx, headline: bool):
         res["decode"] = head["decode"]
         return res, head, st
     layers = list(range(L))
+    c.patch_range_next()
     tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2)
     if headline:
-        patch = torch.empty(patch_capacity(S, L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+        patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         dm = torch.full((B,), -1, dtype=torch.int32)
         dm[torch.from_numpy(st.batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
         head = timed_steps(c, st, tgt, layers, patch, B_new, dst_map=dm.cuda())
@@ -895,7 +952,7 @@ def run_longctx8b(c: Ctx, headline: bool):
     dmap = torch.full((B_new,), -1, dtype=torch.int32)
     dmap[torch.from_numpy(live)] = torch.arange(len(live), dtype=torch.int32)
     dmap = dmap.cuda()
-    patch = torch.empty(patch_capacity(len(live), L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
+    patch = c.big_u8(patch_capacity(len(live), L, cfg.blk_bytes))
     live32 = torch.from_numpy(live.astype(np.int32)).cuda()
     applied0 = P.pipelive_kv_read_state(tgt).t_applied
     res["round0"] = time_patch_round(c, st.region, tgt, live32, 0, layers, patch, dmap, 2, cfg.blk_bytes, B_new)
@@ -1147,7 +1204,7 @@ def main():
     if args.placement_probe:
         print(json.dumps({"placement_probe": run_placement_probe(c)}), flush=True)
         return
-    placement = {"warmup_GiB": 0}
+    placement = {"patch_buffer_ways": int(args.patch_ways), "patch_buffer_parts": args.patch_parts, "warmup_GiB": 0}
     if args.placement_warmup_gib > 0:
         free_b = torch.cuda.mem_get_info()[0]
         gib = min(args.placement_warmup_gib, int(free_b * 0.9) >> 30)
@@ -1155,8 +1212,8 @@ def main():
             ballast = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
             del ballast
             c.free_all()
-            placement = {"warmup_GiB": gib,
-                         "note": "one allocation of this size made and freed before the first pool is allocated"}
+            placement.update({"warmup_GiB": gib,
+                              "note": "one allocation of this size made and freed before the first pool is allocated"})
     runners = {"stage70b": run_stage70b, "stage8b": run_stage8b, "resize8b": run_resize8b, "longctx8b": run_longctx8b}
     headline_name = HEADLINE if args.config == "all" else args.config
     if headline_name not in runners:
@@ -1189,6 +1246,7 @@ def main():
         result["cpu_baseline"] = head["cpu_baseline"]
     del st
     c.free_all()
+    c.patch_range_close()
     if args.config == "all" and not args.decode_only:
         for name in ALL_CONFIGS:
             if name == headline_name:
@@ -1204,6 +1262,7 @@ def main():
                 configs[name] = r
                 del s2
             c.free_all()
+            c.patch_range_close()
             if name == "resize8b" and not args.core_only:
                 configs[name]["sparse_pool"] = run_resize8b_sparse(c)
                 c.free_all()
@@ -1211,6 +1270,7 @@ def main():
     if getattr(c, "prefill_pending", False):
         configs["stage8b"]["prefill"] = run_prefill(c, c.pin.CONFIGS["stage8b"])
         c.free_all()
+    c.patch_range_close()
     result["configs"] = configs
     bar = {}
     for name, r in configs.items():

@@ -306,6 +306,40 @@ int64_t pipelive_vmm_pool_allocated(const pipelive_vmm_pool_t *pool);
 /* first address of the pool's range (position i lies at base + i * block_bytes); 0 for a null pool */
 uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *pool);
 
+/* -------------------------------------------------------------------------
+ * Striped device range: memory placement for MI355X (not from the paper; for
+ * callers that allocate KV pools and patch buffers).  On this part a copy
+ * whose reads and writes all fall into one third of the device memory runs at
+ * 0.64 of the HBM peak, one whose traffic is spread over the thirds at
+ * 0.77-0.81.  A striped range is one virtually contiguous range of device
+ * memory (virtual memory management calls, like the pool above) cut into
+ * pieces of piece_bytes; piece j belongs to part j mod ways, and each part is
+ * backed by one run of physical memory.  Whatever lies in the range - a patch
+ * buffer, a pool, any mix - has its traffic spread over the parts.  The parts
+ * can be backed one by one (back_now = 0, then pipelive_striped_range_back),
+ * so that what the caller allocates in between lies between them in physical
+ * memory: the driver hands memory out in the order of the requests.  The
+ * caller carves its buffers out of [base, base + bytes) once every part is
+ * backed; the kernels see ordinary device addresses.
+ *
+ * bytes        rounded up to a multiple of piece_bytes
+ * piece_bytes  a multiple of 2 MiB (E_INVAL otherwise); 64 MiB - 1 GiB
+ * ways         1 (plain order) .. 64
+ * back_now     1: every part is backed before the call returns
+ * E_NOSPACE if the device is out of memory, E_HIP for any other runtime error;
+ * nothing of the failing call stays allocated.  Host-side driver calls (of the
+ * order of a millisecond per piece): at start-up, not in the serving loop.
+ * destroy unmaps and releases everything; no kernel may be using the range. */
+typedef struct pipelive_striped_range pipelive_striped_range_t;
+int32_t pipelive_striped_range_create(size_t bytes, size_t piece_bytes, int32_t ways, int32_t back_now,
+                                      pipelive_striped_range_t **out);
+/* back part `part` (0 .. ways-1) of a range created with back_now = 0; a part that is backed already is left alone */
+int32_t pipelive_striped_range_back(pipelive_striped_range_t *range, int32_t part);
+void pipelive_striped_range_destroy(pipelive_striped_range_t *range);
+/* first address and size of the range; 0 for a null range */
+uint64_t pipelive_striped_range_base(const pipelive_striped_range_t *range);
+size_t pipelive_striped_range_bytes(const pipelive_striped_range_t *range);
+
 /* Effective KV utilisation (Sec. 7.5, effects of layer stacking): tokens held
  * divided by token slots of the blocks the sequences occupy,
  *   sum_s n_s / sum_s ceil(n_s / block_tokens) * block_tokens ;  1.0 when no

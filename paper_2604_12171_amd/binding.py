@@ -34,7 +34,9 @@ EXPORTS = [
     "pipelive_max_blocks", "pipelive_kv_mark_dirty", "pipelive_patch_max_blocks",
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state", "pipelive_kv_tokens_applied",
     "pipelive_vmm_backing_bytes", "pipelive_vmm_pool_create", "pipelive_vmm_pool_destroy", "pipelive_vmm_pool_alloc",
-    "pipelive_vmm_pool_free", "pipelive_vmm_pool_allocated", "pipelive_vmm_pool_base", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
+    "pipelive_vmm_pool_free", "pipelive_vmm_pool_allocated", "pipelive_vmm_pool_base",
+    "pipelive_striped_range_create", "pipelive_striped_range_back", "pipelive_striped_range_destroy",
+    "pipelive_striped_range_base", "pipelive_striped_range_bytes", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
     "pipelive_kv_clear_status", "pipelive_plan_reconfig", "pipelive_converged", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
 ]
 
@@ -156,6 +158,16 @@ def load(path: str | None = None):
     L.pipelive_vmm_pool_allocated.argtypes = [vp]
     L.pipelive_vmm_pool_base.restype = C.c_uint64
     L.pipelive_vmm_pool_base.argtypes = [vp]
+    L.pipelive_striped_range_create.restype = i32
+    L.pipelive_striped_range_create.argtypes = [sz, sz, i32, i32, C.POINTER(vp)]
+    L.pipelive_striped_range_back.restype = i32
+    L.pipelive_striped_range_back.argtypes = [vp, i32]
+    L.pipelive_striped_range_destroy.restype = None
+    L.pipelive_striped_range_destroy.argtypes = [vp]
+    L.pipelive_striped_range_base.restype = C.c_uint64
+    L.pipelive_striped_range_base.argtypes = [vp]
+    L.pipelive_striped_range_bytes.restype = sz
+    L.pipelive_striped_range_bytes.argtypes = [vp]
     L.pipelive_kv_utilization.restype = C.c_double
     L.pipelive_kv_utilization.argtypes = [vp, i64, i32]
     L.pipelive_stacked_block_tokens.restype = i64
@@ -404,6 +416,58 @@ class _DeviceSpan:
     def __init__(self, addr: int, nbytes: int):
         self.__cuda_array_interface__ = {"shape": (int(nbytes) // 2,), "typestr": "<i2",
                                          "data": (int(addr), False), "version": 2}
+
+
+class StripedRange:
+    """One pipelive_striped_range and a bump allocator over it: tensors carved out of a virtually
+    contiguous range whose pieces alternate between `ways` runs of physical memory.  With
+    ``back_now=False`` the runs are backed one by one with :meth:`back`; what the caller allocates in
+    between lies between them.  The tensors are views without ownership: keep the range alive as
+    long as they are in use."""
+
+    def __init__(self, nbytes: int, ways: int = 3, piece_bytes: int = 64 << 20, back_now: bool = True):
+        h = C.c_void_p()
+        _check(load().pipelive_striped_range_create(int(nbytes), int(piece_bytes), int(ways), int(back_now),
+                                                    C.byref(h)))
+        self.handle, self.ways = h, int(ways)
+        self.backed = set(range(self.ways)) if back_now else set()
+        self.base = int(load().pipelive_striped_range_base(h))
+        self.nbytes = int(load().pipelive_striped_range_bytes(h))
+        self.used = 0
+
+    def back(self, part: int) -> None:
+        _check(load().pipelive_striped_range_back(self.handle, int(part)))
+        self.backed.add(int(part))
+
+    def room(self, align: int = 4096) -> int:
+        return self.nbytes - (self.used + align - 1) // align * align
+
+    def empty(self, numel: int, dtype=torch.uint8, align: int = 4096):
+        """1-D tensor of `numel` elements at the next `align`-byte boundary of the range (every part
+        must be backed by now)"""
+        if len(self.backed) != self.ways:   # a kernel that touched an unbacked piece would fault
+            raise PipeliveError(E_INVAL)
+        itemsize = torch.empty(0, dtype=dtype).element_size()
+        at = (self.used + align - 1) // align * align
+        nbytes = int(numel) * itemsize
+        if nbytes == 0:
+            return torch.empty(0, dtype=dtype, device="cuda")
+        if at + nbytes > self.nbytes:
+            raise PipeliveError(E_NOSPACE)
+        self.used = at + nbytes
+        t = torch.as_tensor(_DeviceSpan(self.base + at, (nbytes + 1) // 2 * 2), device="cuda")
+        return t.view(torch.uint8)[:nbytes].view(dtype)
+
+    def close(self) -> None:
+        if self.handle:
+            load().pipelive_striped_range_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 # ---- device memory plumbing ------------------------------------------------------
