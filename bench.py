@@ -69,19 +69,13 @@ def parse_args():
     ap.add_argument("--prefill-case", default="both", choices=["both", "prompt512", "chunk512_of_4096"],
                     help="with --prefill-only: which of the two cases")
     ap.add_argument("--decode-iters", type=int, default=50)
-    ap.add_argument("--placement-probe", action="store_true",
-                    help="measure the copy paths of the 70B stage on four successive allocations of the same pools "
-                         "(same kernels, same ids: only the physical placement of the buffers differs)")
-    ap.add_argument("--patch-ways", type=int, default=3,
-                    help="runs of physical memory the patch buffers of a workload are striped over, backed "
-                         "before, between and behind its pools (0: the buffers are torch allocations)")
-    ap.add_argument("--patch-parts", default="0,2",
-                    help="how many of those runs are backed before the source pool, between the pools (the rest "
-                         "behind the target pool)")
-    ap.add_argument("--placement-warmup-gib", type=int, default=64,
-                    help="allocate and free this many GiB before the first pool is allocated (0: not). The "
-                         "first 48-64 GiB a process is handed lie where in-pool copies run at 0.63 instead of "
-                         "0.78 of the HBM peak on this part; a server would do the same once at start-up")
+    ap.add_argument("--arena-gib", type=int, default=-1,
+                    help="size of the region-aware arena the pools and patch buffers are carved out of "
+                         "(-1: the free device memory less --arena-reserve-gib; 0: no arena, torch allocations)")
+    ap.add_argument("--arena-reserve-gib", type=int, default=20,
+                    help="device memory left outside the arena (tables, queries, workspaces, the stacked pool)")
+    ap.add_argument("--arena-piece-mib", type=int, default=64, help="piece size of the arena")
+    ap.add_argument("--arena-probe-mib", type=int, default=1024, help="size of the stretches the arena's probe times")
     ap.add_argument("--core-only", action="store_true",
                     help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
                          "stacked pool, 4-layer rounds, sparse pool)")
@@ -139,44 +133,58 @@ class Ctx:
         gc.collect()
         self.torch.cuda.empty_cache()
 
-    # ---- Placement of a workload's patch buffers: one striped range (64 MiB pieces over three runs of
-    # physical memory) whose runs are backed before the source pool, between the pools and behind the
-    # target pool, so that a gather's writes and a scatter's reads are spread over the device memory
-    # instead of falling into one place (--patch-ways 0: torch's own allocations).
-    prange = None
-    _parts = 0
+    # ---- Placement: pools and patch buffers are carved out of one region-aware arena (pieces of 1 GiB that
+    # the library sorts by the region of the device memory they lie in).  The KV blocks of a layer go into one
+    # region, consecutive layers into different ones: a decode launch then reads one region, and the copies,
+    # which work on all layers at once, use all of them.  Patch buffers go into the spread zone, whose pieces
+    # take the regions in turn.  (--arena-gib 0: every buffer is a torch allocation of its own.)
+    arena = None
 
-    def patch_range_open(self, nbytes):
-        self.patch_range_close()
-        ways = int(getattr(self.args, "patch_ways", 0))
-        if ways > 0:
-            self.prange = self.P.StripedRange(int(nbytes) + (64 << 20), ways=ways, back_now=False)
-            self._parts = 0
-            self._sched = [int(x) for x in str(getattr(self.args, "patch_parts", "0,2")).split(",")]
-            self.patch_range_next()
+    def arena_open(self):
+        gib = int(self.args.arena_gib)
+        if gib == 0:
+            return {"arena_GiB": 0}
+        free_b = self.torch.cuda.mem_get_info()[0]
+        if gib < 0:
+            gib = max(1, (free_b >> 30) - int(self.args.arena_reserve_gib))
+        self.arena = self.P.Arena(gib << 30, piece_bytes=int(self.args.arena_piece_mib) << 20,
+                                  probe_bytes=int(self.args.arena_probe_mib) << 20)
+        info = self.arena.info()
+        log(f"[arena] {gib} GiB in {info['n_pieces']} pieces, classes {info['class_pieces']}, probe {info['probe_ms']:.0f} ms, "
+            f"pair copy {info['rate_same_GBps']:.0f} (same region) / {info['rate_other_GBps']:.0f} GB/s")
+        return {"arena_GiB": gib, "piece_MiB": int(self.args.arena_piece_mib), "probe_MiB": int(self.args.arena_probe_mib), **info,
+                "policy": "layer l of a pool in region l mod n_classes; patch buffers in the spread zone"}
 
-    def patch_range_next(self, rest=False):
-        """back the runs of the next point of the schedule (all remaining ones with rest=True)"""
-        if self.prange is None:
-            return
-        n = self.prange.ways if rest or not self._sched else self._sched.pop(0)
-        while n > 0 and self._parts < self.prange.ways:
-            self.prange.back(self._parts)
-            self._parts += 1
-            n -= 1
-
-    def patch_range_close(self):
-        if self.prange is not None:
+    def arena_layout(self, spread_bytes):
+        """start of a workload: nothing carved out of the arena is in use any more; `spread_bytes` of it
+        (plus a margin) become the spread zone, the rest the per-region zones"""
+        if self.arena is not None:
             self.sync()
-            self.prange.close()
-            self.prange = None
+            self.arena.layout(int(spread_bytes) + (256 << 20))
+
+    def alloc(self, numel, dtype, group=None):
+        """1-D device tensor for a large buffer: the arenas of a pool's layer group from a region zone, anything
+        else from the spread zone; a torch allocation when there is no arena or it has no room"""
+        if self.arena is not None:
+            try:
+                if group is None:
+                    return self.arena.empty(numel, dtype)
+                return self.arena.empty_in_class(numel, dtype, prefer=group)
+            except self.P.PipeliveError:
+                pass
+        return self.torch.empty(int(numel), dtype=dtype, device="cuda")
 
     def big_u8(self, n):
-        if self.prange is not None:
-            self.patch_range_next(rest=True)
-            if self.prange.room() >= n:
-                return self.prange.empty(n, self.torch.uint8)
-        return self.torch.empty(n, dtype=self.torch.uint8, device="cuda")
+        return self.alloc(n, self.torch.uint8)
+
+    def free_bytes(self):
+        """(memory the workload definitions count as free, memory a pool can really take): without an arena both
+        are the device's free memory; with one, the first adds what the arena has left and the second is that"""
+        free_b = self.torch.cuda.mem_get_info()[0]
+        if self.arena is None:
+            return free_b, free_b
+        room = self.arena.total_room()
+        return free_b + room, room
 
 
 class Stage:
@@ -189,7 +197,7 @@ class Stage:
         L, S = cfg.num_layers, cfg.num_seqs
         t0 = time.time()
         self.region = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
-                                 self.B, capacity_blocks=self.cap, arenas=arenas)
+                                 self.B, capacity_blocks=self.cap, arenas=arenas, allocator=c.alloc)
         self.batch = pin.draw_batch(cfg, c.seed, num_blocks=self.B, stride_pad=stride_pad)
         c.fill(self.region, cfg, self.batch, c.seed, self.cap, poison_tail=poison)
         c.sync()
@@ -372,8 +380,7 @@ def run_stage70b(c: Ctx, headline: bool):
     ctx = pin.draw_ctx_lens(cfg, c.seed)
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(1.25 * n_live))
-    if not args.decode_only:
-        c.patch_range_open(patch_capacity(int(0.21 * n_live) + S + 8, L, cfg.blk_bytes))
+    c.arena_layout(0 if args.decode_only else patch_capacity(int(0.21 * n_live) + S + 8, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4, stride_pad=2)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -382,8 +389,8 @@ def run_stage70b(c: Ctx, headline: bool):
         head = timed_steps(c, st, None, None, None, None, decode_only=True)
         res["decode"] = head["decode"]
         return res, head, st
-    c.patch_range_next()
-    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3)
+    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3,
+                     allocator=c.alloc)
     fr = pin.geometric_fractions(0.20, 0.01, 6)
     n_r1 = len(pin.draw_dirty_ids(st.batch, c.seed, 1, fr[0]))
     layers = list(range(L))
@@ -578,19 +585,20 @@ def run_stage8b(c: Ctx, headline: bool):
     np, torch, pin, P, args = c.np, c.torch, c.pin, c.P, c.args
     cfg = pin.CONFIGS["stage8b"]
     L, S = cfg.num_layers, cfg.num_seqs
-    weights = torch.empty(stage_weight_bytes(cfg), dtype=torch.uint8, device="cuda")
-    free, _ = torch.cuda.mem_get_info()
     ctx = pin.draw_ctx_lens(cfg, c.seed)
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
-    B = int(0.85 * free // (L * cfg.blk_bytes))
     bulk_fraction = 0.20
+    c.arena_layout(stage_weight_bytes(cfg) + patch_capacity(int((bulk_fraction + 0.01) * n_live) + 2 * S, L, cfg.blk_bytes))
+    weights = c.big_u8(stage_weight_bytes(cfg))
+    free, room = c.free_bytes()
+    B = int(0.85 * free // (L * cfg.blk_bytes))
     if not args.decode_only:
         # the migration target, the patch buffers and the stacked leg must fit beside the pool
-        extra = n_live * L * cfg.blk_bytes * (1.0 + bulk_fraction + 0.05) + (8 << 30)
-        B = min(B, int((free - extra) // (L * cfg.blk_bytes)))
+        extra = n_live * L * cfg.blk_bytes * (1.0 + bulk_fraction + 0.05) + ((8 << 30) if c.arena is None else (1 << 30))
+        B = min(B, int((room - extra) // (L * cfg.blk_bytes)))
+    else:
+        B = min(B, int((room - (1 << 30)) // (L * cfg.blk_bytes)))
     B = max(B, int(math.ceil(n_live * 1.3)))
-    if not args.decode_only:
-        c.patch_range_open(patch_capacity(int((bulk_fraction + 0.01) * n_live) + 2 * S, L, cfg.blk_bytes) + (64 << 20))
     st = Stage(c, cfg, B, arenas=4)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "free_after_weights_GiB": round(free / 2**30, 1), "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -600,8 +608,8 @@ def run_stage8b(c: Ctx, headline: bool):
         return res, head, st
     Lm = 4
     mig_layers = list(range(L - Lm, L))
-    c.patch_range_next()
-    target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2)
+    target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2,
+                        allocator=c.alloc)
     dst_map = torch.full((B,), -1, dtype=torch.int32)
     dst_map[torch.from_numpy(st.batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
     dst_map = dst_map.cuda()
@@ -831,8 +839,7 @@ def run_resize8b(c: Ctx, headline: bool):
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(n_live / 0.75))
     B_new = B * 16 // 20
-    if headline and not args.decode_only:
-        c.patch_range_open(patch_capacity(S, L, cfg.blk_bytes))
+    c.arena_layout(patch_capacity(S, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4, stride_pad=2)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens, "pool_reading": "tight pool: B = ceil(n_live / 0.75)"}
@@ -842,8 +849,8 @@ def run_resize8b(c: Ctx, headline: bool):
         res["decode"] = head["decode"]
         return res, head, st
     if headline:
-        c.patch_range_next()
-        tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=2)
+        tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=2,
+                         allocator=c.alloc)
         patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         head = timed_steps(c, st, tgt, list(range(L)), patch, B_new)
         maybe_cpu_baseline(c, st, head)
@@ -894,9 +901,10 @@ def run_resize8b_sparse(c: Ctx):
     np, torch, pin, P, args = c.np, c.torch, c.pin, c.P, c.args
     cfg = pin.CONFIGS["resize8b"]
     L = cfg.num_layers
-    weights = torch.empty(stage_weight_bytes(cfg), dtype=torch.uint8, device="cuda")
-    free, _ = torch.cuda.mem_get_info()
-    B = int(0.85 * free // (L * cfg.blk_bytes))
+    c.arena_layout(stage_weight_bytes(cfg))
+    weights = c.big_u8(stage_weight_bytes(cfg))
+    free, room = c.free_bytes()
+    B = min(int(0.85 * free // (L * cfg.blk_bytes)), int((room - (1 << 30)) // (L * cfg.blk_bytes)))
     st = Stage(c, cfg, B, arenas=4)
     out = {"pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "decode": st.time_decode(10, args.decode_iters), "resize": st.time_shrink(int(B * 0.8), 5)}
@@ -913,8 +921,7 @@ def run_longctx8b(c: Ctx, headline: bool):
     n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
     B = int(math.ceil(n_live / 0.70))
     B_new = int(B * 0.75)
-    if not args.decode_only:
-        c.patch_range_open(patch_capacity(n_live + S, L, cfg.blk_bytes))
+    c.arena_layout(0 if args.decode_only else patch_capacity(n_live + S, L, cfg.blk_bytes) + patch_capacity(S, L, cfg.blk_bytes))
     st = Stage(c, cfg, B, arenas=4)
     res = {"workload": _wl_name(cfg), "pool_blocks_per_layer": B, "pool_GiB": round(B * L * cfg.blk_bytes / 2**30, 1),
            "live_blocks_per_layer": n_live, "tokens": st.tokens}
@@ -924,8 +931,8 @@ def run_longctx8b(c: Ctx, headline: bool):
         res["decode"] = head["decode"]
         return res, head, st
     layers = list(range(L))
-    c.patch_range_next()
-    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2)
+    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2,
+                     allocator=c.alloc)
     if headline:
         patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         dm = torch.full((B,), -1, dtype=torch.int32)
@@ -969,35 +976,6 @@ def run_longctx8b(c: Ctx, headline: bool):
         raise RuntimeError("longctx8b: counters or status wrong")
     del tgt, patch
     return res, head, None
-
-
-def run_placement_probe(c: Ctx):
-    """The 70B stage's shrink and a 20 % patch round on four successive allocations of the same pools."""
-    np, torch, pin, P = c.np, c.torch, c.pin, c.P
-    cfg = pin.CONFIGS["stage70b"]
-    L = cfg.num_layers
-    ctx = pin.draw_ctx_lens(cfg, c.seed)
-    n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
-    B = int(math.ceil(1.25 * n_live))
-    out = []
-    keep = []
-    for k in range(4):
-        st = Stage(c, cfg, B, arenas=4, poison=False)
-        tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3)
-        ids = torch.from_numpy(pin.draw_dirty_ids(st.batch, c.seed, 1, 0.20).astype(np.int32)).cuda()
-        patch = torch.empty(patch_capacity(ids.numel(), L, cfg.blk_bytes), dtype=torch.uint8, device="cuda")
-        r = time_patch_round(c, st.region, tgt, ids, 0, list(range(L)), patch, None, 5, cfg.blk_bytes, B)
-        z = st.time_shrink(int(B * 0.8), 5)
-        out.append({"allocation": k, "collect_frac_of_peak": r["collect_frac_of_peak"],
-                    "apply_frac_of_peak": r["apply_frac_of_peak"], "resize_frac_of_peak": z["frac_of_peak"],
-                    "source_arena0_addr": hex(st.region.arenas[0].data_ptr()), "patch_addr": hex(patch.data_ptr())})
-        log(f"[placement] {out[-1]}")
-        del st, tgt, patch
-        if k == 1:   # the third and fourth round get their memory while a 40 GiB hole is held elsewhere
-            c.free_all()
-            keep.append(torch.empty(40 << 30, dtype=torch.uint8, device="cuda"))
-        c.free_all()
-    return out
 
 
 def run_tiny(c: Ctx):
@@ -1201,19 +1179,7 @@ def main():
     if args.prefill_only:
         print(json.dumps({"prefill": run_prefill(c, c.pin.CONFIGS["stage8b"])}), flush=True)
         return
-    if args.placement_probe:
-        print(json.dumps({"placement_probe": run_placement_probe(c)}), flush=True)
-        return
-    placement = {"patch_buffer_ways": int(args.patch_ways), "patch_buffer_parts": args.patch_parts, "warmup_GiB": 0}
-    if args.placement_warmup_gib > 0:
-        free_b = torch.cuda.mem_get_info()[0]
-        gib = min(args.placement_warmup_gib, int(free_b * 0.9) >> 30)
-        if gib > 0:
-            ballast = torch.empty(gib << 30, dtype=torch.uint8, device="cuda")
-            del ballast
-            c.free_all()
-            placement.update({"warmup_GiB": gib,
-                              "note": "one allocation of this size made and freed before the first pool is allocated"})
+    placement = c.arena_open()
     runners = {"stage70b": run_stage70b, "stage8b": run_stage8b, "resize8b": run_resize8b, "longctx8b": run_longctx8b}
     headline_name = HEADLINE if args.config == "all" else args.config
     if headline_name not in runners:
@@ -1246,7 +1212,6 @@ def main():
         result["cpu_baseline"] = head["cpu_baseline"]
     del st
     c.free_all()
-    c.patch_range_close()
     if args.config == "all" and not args.decode_only:
         for name in ALL_CONFIGS:
             if name == headline_name:
@@ -1262,7 +1227,6 @@ def main():
                 configs[name] = r
                 del s2
             c.free_all()
-            c.patch_range_close()
             if name == "resize8b" and not args.core_only:
                 configs[name]["sparse_pool"] = run_resize8b_sparse(c)
                 c.free_all()
@@ -1270,7 +1234,6 @@ def main():
     if getattr(c, "prefill_pending", False):
         configs["stage8b"]["prefill"] = run_prefill(c, c.pin.CONFIGS["stage8b"])
         c.free_all()
-    c.patch_range_close()
     result["configs"] = configs
     bar = {}
     for name, r in configs.items():

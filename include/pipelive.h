@@ -307,38 +307,71 @@ int64_t pipelive_vmm_pool_allocated(const pipelive_vmm_pool_t *pool);
 uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *pool);
 
 /* -------------------------------------------------------------------------
- * Striped device range: memory placement for MI355X (not from the paper; for
- * callers that allocate KV pools and patch buffers).  On this part a copy
- * whose reads and writes all fall into one third of the device memory runs at
- * 0.64 of the HBM peak, one whose traffic is spread over the thirds at
- * 0.77-0.81.  A striped range is one virtually contiguous range of device
- * memory (virtual memory management calls, like the pool above) cut into
- * pieces of piece_bytes; piece j belongs to part j mod ways, and each part is
- * backed by one run of physical memory.  Whatever lies in the range - a patch
- * buffer, a pool, any mix - has its traffic spread over the parts.  The parts
- * can be backed one by one (back_now = 0, then pipelive_striped_range_back),
- * so that what the caller allocates in between lies between them in physical
- * memory: the driver hands memory out in the order of the requests.  The
- * caller carves its buffers out of [base, base + bytes) once every part is
- * backed; the kernels see ordinary device addresses.
+ * Region-aware device arena: memory placement for MI355X (not from the paper;
+ * for callers that allocate KV pools and patch buffers).  The 288 GB of this
+ * part behave as three regions of 96 GB.  A copy whose reads and writes all
+ * fall into one region runs at 0.64-0.70 of the HBM peak, one whose traffic is
+ * spread over the regions at 0.78-0.80; a kernel that only reads (decode
+ * attention) is fastest, 0.80 against 0.73, when all it reads in one launch
+ * lies in ONE region; and which region an allocation lands in depends on what
+ * the process, and the one before it, allocated earlier.
+ * An arena is one virtually contiguous range made of physical pieces of
+ * piece_bytes.  With probe_bytes > 0 the call times, for pairs of stretches
+ * of probe_bytes (consecutive pieces as the driver handed them out), a copy
+ * that runs inside both at once (slow: same region) and sorts the pieces into
+ * classes that way.  The range is laid out in zones:
+ *   zone 0, the spread zone: consecutive pieces come from the classes in turn
+ *           (each class in proportion to its size) - for buffers a copy
+ *           streams through, such as patch buffers;
+ *   zone 1 + c: the remaining pieces of class c - for what one launch reads
+ *           alone, such as the KV blocks of one layer.  A pool whose layers
+ *           take the class zones in turn gives decode its one region per
+ *           launch and the copies, which work on all layers at once, all
+ *           regions per launch.
+ * pipelive_arena_layout sets the size of the spread zone (create leaves the
+ * whole range in it) and remaps the pieces accordingly; the caller carves its
+ * buffers out of the zones.  The kernels see ordinary device addresses; the
+ * result of every library call is the same with or without an arena.
  *
- * bytes        rounded up to a multiple of piece_bytes
- * piece_bytes  a multiple of 2 MiB (E_INVAL otherwise); 64 MiB - 1 GiB
- * ways         1 (plain order) .. 64
- * back_now     1: every part is backed before the call returns
+ * bytes        rounded up to a multiple of piece_bytes; all of it is backed
+ *              by physical memory when create returns
+ * piece_bytes  a multiple of 2 MiB (E_INVAL otherwise): the grain at which the
+ *              spread zone alternates between the classes; 64 MiB in the bench
+ * probe_bytes  0: no probe, one class.  Otherwise a multiple of piece_bytes
+ *              (E_INVAL otherwise), large enough to time: 1 GiB is what the
+ *              bench uses; below 256 MiB the classes found are noise (harmless:
+ *              only the order of the pieces depends on them).  About 2 ms per
+ *              GiB of the range: device work on the null stream, the call
+ *              returns when it is done; the device should be idle otherwise.
+ *              A range shorter than two such stretches is not probed
+ * spread_bytes rounded up to whole pieces, at most the range
  * E_NOSPACE if the device is out of memory, E_HIP for any other runtime error;
- * nothing of the failing call stays allocated.  Host-side driver calls (of the
- * order of a millisecond per piece): at start-up, not in the serving loop.
- * destroy unmaps and releases everything; no kernel may be using the range. */
-typedef struct pipelive_striped_range pipelive_striped_range_t;
-int32_t pipelive_striped_range_create(size_t bytes, size_t piece_bytes, int32_t ways, int32_t back_now,
-                                      pipelive_striped_range_t **out);
-/* back part `part` (0 .. ways-1) of a range created with back_now = 0; a part that is backed already is left alone */
-int32_t pipelive_striped_range_back(pipelive_striped_range_t *range, int32_t part);
-void pipelive_striped_range_destroy(pipelive_striped_range_t *range);
-/* first address and size of the range; 0 for a null range */
-uint64_t pipelive_striped_range_base(const pipelive_striped_range_t *range);
-size_t pipelive_striped_range_bytes(const pipelive_striped_range_t *range);
+ * nothing of a failing create stays allocated (after a failing layout the
+ * arena can only be destroyed).  At start-up or between workloads, not in the
+ * serving loop: create and layout wait for the device and are host-side driver
+ * calls of the order of a millisecond per piece.  The contents of the range
+ * are undefined after either; no kernel may be using the range during layout
+ * or destroy, which unmaps and releases everything. */
+#define PIPELIVE_ARENA_MAX_CLASSES 4
+typedef struct pipelive_arena pipelive_arena_t;
+typedef struct {
+  int32_t n_pieces, n_classes;
+  int32_t class_pieces[PIPELIVE_ARENA_MAX_CLASSES]; /* pieces per class */
+  float probe_ms;        /* time the probe took (0 without probe) */
+  float rate_same_GBps;  /* mean rate (read + written) of the pair copies judged "same region" ... */
+  float rate_other_GBps; /* ... and of those judged "different regions"; 0 if there was no contrast */
+} pipelive_arena_info_t;
+int32_t pipelive_arena_create(size_t bytes, size_t piece_bytes, size_t probe_bytes, pipelive_arena_t **out);
+int32_t pipelive_arena_layout(pipelive_arena_t *arena, size_t spread_bytes);
+void pipelive_arena_destroy(pipelive_arena_t *arena);
+/* first address and size of the range; 0 for a null arena */
+uint64_t pipelive_arena_base(const pipelive_arena_t *arena);
+size_t pipelive_arena_bytes(const pipelive_arena_t *arena);
+int32_t pipelive_arena_info(const pipelive_arena_t *arena, pipelive_arena_info_t *out);
+/* byte offset from base and size of zone 0 .. n_classes (a zone may be empty); E_INVAL for any other zone */
+int32_t pipelive_arena_zone(const pipelive_arena_t *arena, int32_t zone, uint64_t *offset, uint64_t *bytes);
+/* class (0 .. n_classes-1) of the piece at [base + piece * piece_bytes, ...); E_INVAL outside the range */
+int32_t pipelive_arena_piece_class(const pipelive_arena_t *arena, int64_t piece);
 
 /* Effective KV utilisation (Sec. 7.5, effects of layer stacking): tokens held
  * divided by token slots of the blocks the sequences occupy,

@@ -35,8 +35,8 @@ EXPORTS = [
     "pipelive_kv_patch_collect", "pipelive_kv_patch_apply", "pipelive_kv_read_state", "pipelive_kv_tokens_applied",
     "pipelive_vmm_backing_bytes", "pipelive_vmm_pool_create", "pipelive_vmm_pool_destroy", "pipelive_vmm_pool_alloc",
     "pipelive_vmm_pool_free", "pipelive_vmm_pool_allocated", "pipelive_vmm_pool_base",
-    "pipelive_striped_range_create", "pipelive_striped_range_back", "pipelive_striped_range_destroy",
-    "pipelive_striped_range_base", "pipelive_striped_range_bytes", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
+    "pipelive_arena_create", "pipelive_arena_layout", "pipelive_arena_destroy", "pipelive_arena_base",
+    "pipelive_arena_bytes", "pipelive_arena_info", "pipelive_arena_zone", "pipelive_arena_piece_class", "pipelive_kv_utilization", "pipelive_stacked_block_tokens",
     "pipelive_kv_clear_status", "pipelive_plan_reconfig", "pipelive_converged", "pipelive_strerror", "pipelive_last_hip_error", "pipelive_device_ok",
 ]
 
@@ -68,6 +68,11 @@ class PatchHdr(C.Structure):
 class ReconfigPlan(C.Structure):
     _fields_ = [("feasible", C.c_int32), ("need_shrink", C.c_int32), ("b_shrink", C.c_int64),
                 ("b_new", C.c_int64), ("n_mig", C.c_int32), ("n_del", C.c_int32)]
+
+
+class ArenaInfo(C.Structure):
+    _fields_ = [("n_pieces", C.c_int32), ("n_classes", C.c_int32), ("class_pieces", C.c_int32 * 4),
+                ("probe_ms", C.c_float), ("rate_same_GBps", C.c_float), ("rate_other_GBps", C.c_float)]
 
 
 class KVState(C.Structure):
@@ -158,16 +163,22 @@ def load(path: str | None = None):
     L.pipelive_vmm_pool_allocated.argtypes = [vp]
     L.pipelive_vmm_pool_base.restype = C.c_uint64
     L.pipelive_vmm_pool_base.argtypes = [vp]
-    L.pipelive_striped_range_create.restype = i32
-    L.pipelive_striped_range_create.argtypes = [sz, sz, i32, i32, C.POINTER(vp)]
-    L.pipelive_striped_range_back.restype = i32
-    L.pipelive_striped_range_back.argtypes = [vp, i32]
-    L.pipelive_striped_range_destroy.restype = None
-    L.pipelive_striped_range_destroy.argtypes = [vp]
-    L.pipelive_striped_range_base.restype = C.c_uint64
-    L.pipelive_striped_range_base.argtypes = [vp]
-    L.pipelive_striped_range_bytes.restype = sz
-    L.pipelive_striped_range_bytes.argtypes = [vp]
+    L.pipelive_arena_create.restype = i32
+    L.pipelive_arena_create.argtypes = [sz, sz, sz, C.POINTER(vp)]
+    L.pipelive_arena_layout.restype = i32
+    L.pipelive_arena_layout.argtypes = [vp, sz]
+    L.pipelive_arena_zone.restype = i32
+    L.pipelive_arena_zone.argtypes = [vp, i32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+    L.pipelive_arena_destroy.restype = None
+    L.pipelive_arena_destroy.argtypes = [vp]
+    L.pipelive_arena_base.restype = C.c_uint64
+    L.pipelive_arena_base.argtypes = [vp]
+    L.pipelive_arena_bytes.restype = sz
+    L.pipelive_arena_bytes.argtypes = [vp]
+    L.pipelive_arena_info.restype = i32
+    L.pipelive_arena_info.argtypes = [vp, C.POINTER(ArenaInfo)]
+    L.pipelive_arena_piece_class.restype = i32
+    L.pipelive_arena_piece_class.argtypes = [vp, i64]
     L.pipelive_kv_utilization.restype = C.c_double
     L.pipelive_kv_utilization.argtypes = [vp, i64, i32]
     L.pipelive_stacked_block_tokens.restype = i64
@@ -418,49 +429,81 @@ class _DeviceSpan:
                                          "data": (int(addr), False), "version": 2}
 
 
-class StripedRange:
-    """One pipelive_striped_range and a bump allocator over it: tensors carved out of a virtually
-    contiguous range whose pieces alternate between `ways` runs of physical memory.  With
-    ``back_now=False`` the runs are backed one by one with :meth:`back`; what the caller allocates in
-    between lies between them.  The tensors are views without ownership: keep the range alive as
-    long as they are in use."""
+class Arena:
+    """One pipelive_arena and a bump allocator per zone: tensors carved out of a range whose pieces
+    are sorted by the region of the device memory they lie in (zone 0: the regions in turn; zone
+    1 + c: region c only).  The tensors are views without ownership: keep the arena alive, and do
+    not call :meth:`layout` again, as long as they are in use."""
 
-    def __init__(self, nbytes: int, ways: int = 3, piece_bytes: int = 64 << 20, back_now: bool = True):
+    def __init__(self, nbytes: int, piece_bytes: int = 64 << 20, probe_bytes: int = 1 << 30):
         h = C.c_void_p()
-        _check(load().pipelive_striped_range_create(int(nbytes), int(piece_bytes), int(ways), int(back_now),
-                                                    C.byref(h)))
-        self.handle, self.ways = h, int(ways)
-        self.backed = set(range(self.ways)) if back_now else set()
-        self.base = int(load().pipelive_striped_range_base(h))
-        self.nbytes = int(load().pipelive_striped_range_bytes(h))
-        self.used = 0
+        _check(load().pipelive_arena_create(int(nbytes), int(piece_bytes), int(probe_bytes), C.byref(h)))
+        self.handle = h
+        self.piece_bytes = int(piece_bytes)
+        self.base = int(load().pipelive_arena_base(h))
+        self.nbytes = int(load().pipelive_arena_bytes(h))
+        self.n_classes = self.info()["n_classes"]
+        self._read_zones()
 
-    def back(self, part: int) -> None:
-        _check(load().pipelive_striped_range_back(self.handle, int(part)))
-        self.backed.add(int(part))
+    def info(self) -> dict:
+        i = ArenaInfo()
+        _check(load().pipelive_arena_info(self.handle, C.byref(i)))
+        return {"n_pieces": i.n_pieces, "n_classes": i.n_classes,
+                "class_pieces": [int(x) for x in i.class_pieces][:max(1, i.n_classes)],
+                "probe_ms": round(float(i.probe_ms), 1), "rate_same_GBps": round(float(i.rate_same_GBps), 1),
+                "rate_other_GBps": round(float(i.rate_other_GBps), 1)}
 
-    def room(self, align: int = 4096) -> int:
-        return self.nbytes - (self.used + align - 1) // align * align
+    def _read_zones(self) -> None:
+        self.zones = []   # [offset, bytes, used] per zone
+        for z in range(self.n_classes + 1):
+            off, n = C.c_uint64(), C.c_uint64()
+            _check(load().pipelive_arena_zone(self.handle, z, C.byref(off), C.byref(n)))
+            self.zones.append([int(off.value), int(n.value), 0])
 
-    def empty(self, numel: int, dtype=torch.uint8, align: int = 4096):
-        """1-D tensor of `numel` elements at the next `align`-byte boundary of the range (every part
-        must be backed by now)"""
-        if len(self.backed) != self.ways:   # a kernel that touched an unbacked piece would fault
-            raise PipeliveError(E_INVAL)
+    def layout(self, spread_bytes: int) -> None:
+        """size of the spread zone; everything carved out so far is given up (contents undefined)"""
+        torch.cuda.synchronize()
+        _check(load().pipelive_arena_layout(self.handle, int(spread_bytes)))
+        self._read_zones()
+
+    def piece_class(self, piece: int) -> int:
+        return _check(load().pipelive_arena_piece_class(self.handle, int(piece)))
+
+    def room(self, zone: int = 0, align: int = 4096) -> int:
+        _, n, used = self.zones[zone]
+        return n - (used + align - 1) // align * align
+
+    def total_room(self) -> int:
+        return sum(max(0, self.room(z)) for z in range(len(self.zones)))
+
+    def empty(self, numel: int, dtype=torch.uint8, zone: int = 0, align: int = 4096):
+        """1-D tensor of `numel` elements at the next `align`-byte boundary of the zone"""
         itemsize = torch.empty(0, dtype=dtype).element_size()
-        at = (self.used + align - 1) // align * align
+        off, n, used = self.zones[zone]
+        at = (used + align - 1) // align * align
         nbytes = int(numel) * itemsize
         if nbytes == 0:
             return torch.empty(0, dtype=dtype, device="cuda")
-        if at + nbytes > self.nbytes:
+        if at + nbytes > n:
             raise PipeliveError(E_NOSPACE)
-        self.used = at + nbytes
-        t = torch.as_tensor(_DeviceSpan(self.base + at, (nbytes + 1) // 2 * 2), device="cuda")
+        self.zones[zone][2] = at + nbytes
+        t = torch.as_tensor(_DeviceSpan(self.base + off + at, (nbytes + 1) // 2 * 2), device="cuda")
         return t.view(torch.uint8)[:nbytes].view(dtype)
+
+    def empty_in_class(self, numel: int, dtype=torch.uint8, prefer: int = 0):
+        """like :meth:`empty`, from the zone of class ``prefer % n_classes`` if it has room, else from the
+        class zone with the most room, else from the spread zone"""
+        nbytes = int(numel) * torch.empty(0, dtype=dtype).element_size()
+        first = 1 + int(prefer) % self.n_classes
+        rest = sorted((z for z in range(1, self.n_classes + 1) if z != first), key=lambda z: -self.room(z))
+        for z in [first] + rest + [0]:
+            if self.room(z) >= nbytes:
+                return self.empty(numel, dtype, zone=z)
+        raise PipeliveError(E_NOSPACE)
 
     def close(self) -> None:
         if self.handle:
-            load().pipelive_striped_range_destroy(self.handle)
+            load().pipelive_arena_destroy(self.handle)
             self.handle = None
 
     def __del__(self):
@@ -480,12 +523,15 @@ class KVRegion:
     address is ``base + id * stride``; all ``capacity`` ids are backed.
     ``backing="vmm"``: every physical block is an allocation of its own from a
     :class:`VmmPool` (shuffled positions); only ids below ``num_blocks`` are
-    backed, :meth:`grow_backing` and :meth:`release_tail` follow a resize."""
+    backed, :meth:`grow_backing` and :meth:`release_tail` follow a resize.
+    ``allocator`` (arena backing only): ``allocator(numel, dtype, group)`` returns the 1-D device
+    tensor one arena of layer group ``group`` is laid in (e.g. :meth:`Arena.empty_in_class` with
+    ``prefer=group``); default: torch allocations."""
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
                  capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda",
                  dirty_granularity=DIRTY_BLOCK, share_pool_of: "KVRegion | None" = None,
-                 backing="arena"):
+                 backing="arena", allocator=None):
         import numpy as np
         L = load()
         if not torch.cuda.is_available():
@@ -527,7 +573,10 @@ class KVRegion:
             for g in range(self.groups):
                 for a in range(n_ar):
                     cnt = len(range(a, self.capacity, n_ar))
-                    t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
+                    if allocator is not None:
+                        t = allocator(cnt * phys, torch.int16, g).view(cnt, phys)
+                    else:
+                        t = torch.empty((cnt, phys), dtype=torch.int16, device=self.device)
                     if self._fill is not None:
                         t.fill_(self._fill)
                     self.arenas.append(t)

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libpipelive.so")
-SOURCES = ["api.hip", "attn_decode.hip", "attn_prefill.hip", "kv_resize.hip", "kv_patch.hip", "vmm_pool.hip", "planner.cpp"]
+SOURCES = ["api.hip", "attn_decode.hip", "attn_prefill.hip", "kv_resize.hip", "kv_patch.hip", "vmm_pool.hip", "arena.hip", "planner.cpp"]
 HEADERS = ["internal.h", "kv_copy.h", "scan.h", "attn_common.h"]
 
 FLAGS = [

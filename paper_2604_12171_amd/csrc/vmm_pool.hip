@@ -19,16 +19,6 @@ struct pipelive_vmm_pool {
   hipMemAllocationProp prop = {};
 };
 
-// One virtually contiguous range whose pieces come alternately from `ways` parts of the physical
-// memory the driver hands out for it (placement for copies on MI355X; see the header).
-struct pipelive_striped_range {
-  char *base = nullptr;
-  size_t bytes = 0, piece_bytes = 0;
-  int32_t ways = 1, device = 0;
-  std::vector<hipMemGenericAllocationHandle_t> handle;  // by virtual piece
-  std::vector<uint8_t> mapped;
-};
-
 namespace {
 
 constexpr size_t kBackingUnit = (size_t)2 << 20;
@@ -175,111 +165,6 @@ int32_t pipelive_vmm_pool_free(pipelive_vmm_pool_t *p, int64_t n, const uint64_t
   }
   return rc;
 }
-
-// reserve the address range; no physical memory yet
-static int32_t striped_reserve(size_t bytes, size_t piece_bytes, int32_t ways, pipelive_striped_range_t **out) {
-  if (!out || bytes == 0 || piece_bytes == 0 || piece_bytes % kBackingUnit || ways < 1 || ways > 64)
-    return PIPELIVE_E_INVAL;
-  *out = nullptr;
-  int dev = 0, ok = 0;
-  HIP_TRY(hipGetDevice(&dev));
-  HIP_TRY(hipDeviceGetAttribute(&ok, hipDeviceAttributeVirtualMemoryManagementSupported, dev));
-  if (!ok) {
-    pipelive::set_hip_error("device has no virtual memory management");
-    return PIPELIVE_E_HIP;
-  }
-  const size_t np = (bytes + piece_bytes - 1) / piece_bytes;
-  if (np >= ((size_t)1 << 31)) return PIPELIVE_E_INVAL;
-  pipelive_striped_range *r = new (std::nothrow) pipelive_striped_range;
-  if (!r) return PIPELIVE_E_NOSPACE;
-  r->bytes = np * piece_bytes;
-  r->piece_bytes = piece_bytes;
-  r->ways = ways;
-  r->device = dev;
-  r->handle.resize(np);
-  r->mapped.assign(np, 0);
-  void *va = nullptr;
-  hipError_t e = hipMemAddressReserve(&va, r->bytes, 0, nullptr, 0);
-  if (e != hipSuccess) {
-    delete r;
-    pipelive::set_hip_error(hipGetErrorString(e));
-    return PIPELIVE_E_HIP;
-  }
-  r->base = (char *)va;
-  *out = r;
-  return PIPELIVE_OK;
-}
-
-int32_t pipelive_striped_range_back(pipelive_striped_range_t *r, int32_t part) {
-  if (!r || part < 0 || part >= r->ways) return PIPELIVE_E_INVAL;
-  hipMemAllocationProp prop = {};
-  prop.type = hipMemAllocationTypePinned;
-  prop.location.type = hipMemLocationTypeDevice;
-  prop.location.id = r->device;
-  hipMemAccessDesc ad = {};
-  ad.location = prop.location;
-  ad.flags = hipMemAccessFlagsProtReadWrite;
-  // the pieces of a part are every ways-th piece of the range; the driver hands their memory out in
-  // the order of these requests, one run of physical memory per part
-  const size_t np = r->handle.size();
-  std::vector<size_t> done;
-  hipError_t e = hipSuccess;
-  for (size_t j = (size_t)part; j < np && e == hipSuccess; j += (size_t)r->ways) {
-    if (r->mapped[j]) continue;
-    e = hipMemCreate(&r->handle[j], r->piece_bytes, &prop, 0);
-    if (e != hipSuccess) break;
-    e = hipMemMap(r->base + j * r->piece_bytes, r->piece_bytes, 0, r->handle[j], 0);
-    if (e == hipSuccess) e = hipMemSetAccess(r->base + j * r->piece_bytes, r->piece_bytes, &ad, 1);
-    if (e != hipSuccess) {
-      (void)hipMemUnmap(r->base + j * r->piece_bytes, r->piece_bytes);
-      (void)hipMemRelease(r->handle[j]);
-      break;
-    }
-    r->mapped[j] = 1;
-    done.push_back(j);
-  }
-  if (e != hipSuccess) {  // nothing of this call stays
-    const bool oom = e == hipErrorOutOfMemory;
-    pipelive::set_hip_error(hipGetErrorString(e));
-    for (size_t j : done) {
-      (void)hipMemUnmap(r->base + j * r->piece_bytes, r->piece_bytes);
-      (void)hipMemRelease(r->handle[j]);
-      r->mapped[j] = 0;
-    }
-    (void)hipGetLastError();
-    return oom ? PIPELIVE_E_NOSPACE : PIPELIVE_E_HIP;
-  }
-  return PIPELIVE_OK;
-}
-
-int32_t pipelive_striped_range_create(size_t bytes, size_t piece_bytes, int32_t ways, int32_t back_now,
-                                      pipelive_striped_range_t **out) {
-  int32_t rc = striped_reserve(bytes, piece_bytes, ways, out);
-  if (rc != PIPELIVE_OK || !back_now) return rc;
-  for (int32_t part = 0; part < ways; ++part) {
-    rc = pipelive_striped_range_back(*out, part);
-    if (rc != PIPELIVE_OK) {
-      pipelive_striped_range_destroy(*out);
-      *out = nullptr;
-      return rc;
-    }
-  }
-  return PIPELIVE_OK;
-}
-
-void pipelive_striped_range_destroy(pipelive_striped_range_t *r) {
-  if (!r) return;
-  for (size_t j = 0; j < r->mapped.size(); ++j)
-    if (r->mapped[j]) {
-      (void)hipMemUnmap(r->base + j * r->piece_bytes, r->piece_bytes);
-      (void)hipMemRelease(r->handle[j]);
-    }
-  if (r->base) (void)hipMemAddressFree(r->base, r->bytes);
-  delete r;
-}
-
-uint64_t pipelive_striped_range_base(const pipelive_striped_range_t *r) { return r ? (uint64_t)r->base : 0; }
-size_t pipelive_striped_range_bytes(const pipelive_striped_range_t *r) { return r ? r->bytes : 0; }
 
 int64_t pipelive_vmm_pool_allocated(const pipelive_vmm_pool_t *p) { return p ? p->allocated : -1; }
 uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *p) { return p ? (uint64_t)p->base : 0; }
