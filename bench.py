@@ -75,7 +75,7 @@ def parse_args():
     ap.add_argument("--arena-reserve-gib", type=int, default=20,
                     help="device memory left outside the arena (tables, queries, workspaces, the stacked pool)")
     ap.add_argument("--arena-piece-mib", type=int, default=64, help="piece size of the arena")
-    ap.add_argument("--arena-probe-mib", type=int, default=1024, help="size of the stretches the arena's probe times")
+    ap.add_argument("--arena-probe-mib", type=int, default=256, help="size of the stretches the arena's probe times")
     ap.add_argument("--core-only", action="store_true",
                     help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
                          "stacked pool, 4-layer rounds, sparse pool)")

@@ -435,7 +435,7 @@ class Arena:
     1 + c: region c only).  The tensors are views without ownership: keep the arena alive, and do
     not call :meth:`layout` again, as long as they are in use."""
 
-    def __init__(self, nbytes: int, piece_bytes: int = 64 << 20, probe_bytes: int = 1 << 30):
+    def __init__(self, nbytes: int, piece_bytes: int = 64 << 20, probe_bytes: int = 256 << 20):
         h = C.c_void_p()
         _check(load().pipelive_arena_create(int(nbytes), int(piece_bytes), int(probe_bytes), C.byref(h)))
         self.handle = h
@@ -467,7 +467,10 @@ class Arena:
         self._read_zones()
 
     def piece_class(self, piece: int) -> int:
-        return _check(load().pipelive_arena_piece_class(self.handle, int(piece)))
+        rc = int(load().pipelive_arena_piece_class(self.handle, int(piece)))
+        if rc < 0:
+            raise PipeliveError(rc)
+        return rc
 
     def room(self, zone: int = 0, align: int = 4096) -> int:
         _, n, used = self.zones[zone]

@@ -32,10 +32,14 @@ constexpr size_t kBackingUnit = (size_t)2 << 20;
 constexpr size_t kChunk = 32768;  // bytes one workgroup moves per pass
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// Copies the lower half of piece a into its upper half and the same inside piece b, both at once
-// (chunks of 32 KiB, nontemporal like the library's copy kernels).
-__global__ __launch_bounds__(256) void arena_probe_kernel(char *a, char *b, int32_t chunks_per_piece, size_t half) {
-  for (int32_t c = blockIdx.x; c < 2 * chunks_per_piece; c += gridDim.x) {
+// Copies the lower half of stretch a into its upper half and the same inside stretch b, both at once (chunks of
+// 32 KiB, nontemporal like the library's copy kernels), `passes` times over, so that a launch on short stretches
+// still runs long enough to time.
+__global__ __launch_bounds__(256) void arena_probe_kernel(char *a, char *b, int32_t chunks_per_piece, size_t half,
+                                                          int32_t passes) {
+  const int32_t n = 2 * chunks_per_piece;
+  for (int32_t it = blockIdx.x; it < n * passes; it += gridDim.x) {
+    const int32_t c = it % n;
     char *base = c < chunks_per_piece ? a : b;
     const size_t off = (size_t)(c < chunks_per_piece ? c : c - chunks_per_piece) * kChunk;
     const u32x4 *s = (const u32x4 *)(base + off);
@@ -76,12 +80,13 @@ hipError_t map_in_order(pipelive_arena *r, const std::vector<int32_t> &order) {
 hipError_t pair_rate(pipelive_arena *r, hipEvent_t e0, hipEvent_t e1, size_t a, size_t b, double *rate) {
   const size_t half = r->probe_bytes / 2;
   const int32_t chunks = (int32_t)(half / kChunk);
+  const int32_t passes = (int32_t)std::max<size_t>(1, ((size_t)1 << 29) / r->probe_bytes);  // at least 512 MiB moved per stretch
   float best = 0.f;
   for (int rep = 0; rep < 2; ++rep) {
     hipError_t e = hipEventRecord(e0, nullptr);
     if (e != hipSuccess) return e;
     arena_probe_kernel<<<dim3(4096), dim3(256), 0, nullptr>>>(r->base + a * r->probe_bytes, r->base + b * r->probe_bytes,
-                                                            chunks, half);
+                                                            chunks, half, passes);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = hipEventRecord(e1, nullptr)) != hipSuccess) return e;
     if ((e = hipEventSynchronize(e1)) != hipSuccess) return e;
@@ -89,7 +94,7 @@ hipError_t pair_rate(pipelive_arena *r, hipEvent_t e0, hipEvent_t e1, size_t a, 
     if ((e = hipEventElapsedTime(&ms, e0, e1)) != hipSuccess) return e;
     if (rep > 0 && (best == 0.f || ms < best)) best = ms;
   }
-  *rate = 4.0 * (double)half / ((double)best * 1e-3);
+  *rate = 4.0 * (double)half * passes / ((double)best * 1e-3);
   return hipSuccess;
 }
 
