@@ -147,8 +147,12 @@ class Ctx:
         free_b = self.torch.cuda.mem_get_info()[0]
         if gib < 0:
             gib = max(1, (free_b >> 30) - int(self.args.arena_reserve_gib))
-        self.arena = self.P.Arena(gib << 30, piece_bytes=int(self.args.arena_piece_mib) << 20,
-                                  probe_bytes=int(self.args.arena_probe_mib) << 20)
+        try:
+            self.arena = self.P.Arena(gib << 30, piece_bytes=int(self.args.arena_piece_mib) << 20,
+                                      probe_bytes=int(self.args.arena_probe_mib) << 20)
+        except self.P.PipeliveError as e:   # placement only: the run goes on with torch allocations
+            log(f"[arena] not created ({e}); torch allocations instead")
+            return {"arena_GiB": 0, "note": f"arena of {gib} GiB could not be created: {e}"}
         info = self.arena.info()
         log(f"[arena] {gib} GiB in {info['n_pieces']} pieces, classes {info['class_pieces']}, probe {info['probe_ms']:.0f} ms, "
             f"pair copy {info['rate_same_GBps']:.0f} (same region) / {info['rate_other_GBps']:.0f} GB/s")
