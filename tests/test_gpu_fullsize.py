@@ -89,13 +89,13 @@ def _sample_pairs(cfg, n_pairs, salt):
 class Stage:
     """Device region + tensors of one workload."""
 
-    def __init__(self, cfg, B, capacity=None, arenas=4, stack_k=1, backing="arena", stride_pad=0):
+    def __init__(self, cfg, B, capacity=None, arenas=4, stack_k=1, backing="arena", stride_pad=0, allocator=None):
         self.cfg, self.B = cfg, B
         self.cap = capacity or B
         self.batch = pin.draw_batch(cfg, SEED, num_blocks=B, stride_pad=stride_pad)
         self.region = P.KVRegion(cfg.num_layers, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim,
                                  cfg.block_tokens, B, capacity_blocks=self.cap, arenas=arenas, stack_k=stack_k,
-                                 backing=backing)
+                                 backing=backing, allocator=allocator)
         fill_live_blocks(self.region, cfg, self.batch, SEED, self.cap, poison_tail=True)
         self.table = torch.from_numpy(self.batch.table).cuda()
         self.ctx = torch.from_numpy(self.batch.ctx_lens).cuda()
@@ -367,6 +367,55 @@ def test_stage70b_incremental_patching_six_rounds():
         exp = pin.kv_block_bits(cfg, SEED, B, 0, l, int(b))
         assert np.array_equal(got, exp) or _tail_ok(cfg, st.batch, b, got, exp) or l in (0, 7, L - 1) or int(b) in touched
     del st, tgt, patch
+    torch.cuda.empty_cache()
+
+
+def test_stage70b_placed_by_the_arena_as_the_bench_places_it():
+    """Workload 4 with its pools and patch buffer carved out of a probed region-aware arena the way bench.py
+    does it (layer l in the zone of class l mod n, the patch buffer in the spread zone): decode against the
+    oracle on 64 sampled pairs, a 20 % patch round whose target equals the source, and the 20 % shrink with all
+    state compared with the oracle's.  The placement changes addresses only; every result must be what it is
+    on torch allocations."""
+    cfg = pin.CONFIGS["stage70b"]
+    ctx = pin.draw_ctx_lens(cfg, SEED)
+    n_live = int(((ctx.astype(np.int64) + cfg.block_tokens - 1) // cfg.block_tokens).sum())
+    B = int(math.ceil(1.25 * n_live))
+    L = cfg.num_layers
+    ids = pin.draw_dirty_ids(pin.draw_batch(cfg, SEED, num_blocks=B, stride_pad=2), SEED, 1, 0.20)
+    cap = 64 + 256 + (len(ids) + 8) * (4 + L * cfg.blk_bytes)
+    pool_bytes = B * L * cfg.blk_bytes
+    arena = P.Arena(2 * pool_bytes + cap + (8 << 30))
+    info = arena.info()
+    log(f"stage70b on an arena of {arena.nbytes >> 30} GiB: classes {info['class_pieces']}, probe {info['probe_ms']:.0f} ms")
+    arena.layout(cap + (256 << 20))
+    place = lambda n, dt, g: arena.empty_in_class(n, dt, prefer=g)
+    st = Stage(cfg, B, stride_pad=2, allocator=place)
+    lo, hi = arena.base + arena.zones[1][0], arena.base + arena.nbytes
+    assert all(lo <= t.data_ptr() < hi for t in st.region.arenas)          # every pool arena in a class zone
+    if info["n_classes"] > 1:                                              # a layer's arenas share one zone
+        for g in range(L):
+            zs = {z for t in st.region.arenas[4 * g:4 * g + 4] for z in range(1, len(arena.zones))
+                  if arena.zones[z][0] <= t.data_ptr() - arena.base < arena.zones[z][0] + arena.zones[z][1]}
+            assert len(zs) == 1, (g, zs)
+    st.check_attention(64, salt=14)
+    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3, allocator=place)
+    patch = arena.empty(cap)
+    ids32 = torch.from_numpy(np.asarray(ids, dtype=np.int32)).cuda()
+    P.pipelive_kv_mark_dirty(st.region, ids32, 7)
+    hdr = torch.zeros(64, dtype=torch.uint8).pin_memory()
+    P.pipelive_kv_patch_collect(st.region, list(range(L)), patch, hdr_host=hdr)
+    P.pipelive_kv_patch_apply(tgt, list(range(L)), patch)
+    torch.cuda.synchronize()
+    g = oracle.parse_patch_header(hdr.numpy())
+    assert g["n_blocks"] == len(ids) and g["n_acc_tokens"] == 7 and not g["more_pending"]
+    assert np.array_equal(patch[64:64 + 4 * len(ids)].view(torch.int32).cpu().numpy(), np.sort(ids).astype(np.int32))
+    for l in range(L):
+        assert torch.equal(tgt.read_blocks(l, ids), st.region.read_blocks(l, ids)), l
+    assert P.pipelive_kv_read_state(tgt).t_applied == 7 and len(bitmap_ids(st.region.dirty, B)) == 0
+    _resize_and_check(st, int(B * 0.8), "20 % shrink on arena memory")
+    assert P.pipelive_kv_read_state(st.region).status == 0
+    del st, tgt, patch
+    arena.close()
     torch.cuda.empty_cache()
 
 
