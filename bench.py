@@ -181,6 +181,19 @@ class Ctx:
     def big_u8(self, n):
         return self.alloc(n, self.torch.uint8)
 
+    def placer(self, arenas_per_layer):
+        """allocator for a pool: all arenas of a layer in one region zone (None without an arena)"""
+        if self.arena is None:
+            return None
+        inner = self.arena.placer(arenas_per_layer)
+
+        def alloc(numel, dtype, group):
+            try:
+                return inner(numel, dtype, group)
+            except self.P.PipeliveError:
+                return self.torch.empty(int(numel), dtype=dtype, device="cuda")
+        return alloc
+
     def free_bytes(self):
         """(memory the workload definitions count as free, memory a pool can really take): without an arena both
         are the device's free memory; with one, the first adds what the arena has left and the second is that"""
@@ -201,7 +214,7 @@ class Stage:
         L, S = cfg.num_layers, cfg.num_seqs
         t0 = time.time()
         self.region = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens,
-                                 self.B, capacity_blocks=self.cap, arenas=arenas, allocator=c.alloc)
+                                 self.B, capacity_blocks=self.cap, arenas=arenas, allocator=c.placer(arenas))
         self.batch = pin.draw_batch(cfg, c.seed, num_blocks=self.B, stride_pad=stride_pad)
         c.fill(self.region, cfg, self.batch, c.seed, self.cap, poison_tail=poison)
         c.sync()
@@ -394,7 +407,7 @@ def run_stage70b(c: Ctx, headline: bool):
         res["decode"] = head["decode"]
         return res, head, st
     tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3,
-                     allocator=c.alloc)
+                     allocator=c.placer(3))
     fr = pin.geometric_fractions(0.20, 0.01, 6)
     n_r1 = len(pin.draw_dirty_ids(st.batch, c.seed, 1, fr[0]))
     layers = list(range(L))
@@ -613,7 +626,7 @@ def run_stage8b(c: Ctx, headline: bool):
     Lm = 4
     mig_layers = list(range(L - Lm, L))
     target = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2,
-                        allocator=c.alloc)
+                        allocator=c.placer(2))
     dst_map = torch.full((B,), -1, dtype=torch.int32)
     dst_map[torch.from_numpy(st.batch.live_ids)] = torch.arange(n_live, dtype=torch.int32)
     dst_map = dst_map.cuda()
@@ -854,7 +867,7 @@ def run_resize8b(c: Ctx, headline: bool):
         return res, head, st
     if headline:
         tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=2,
-                         allocator=c.alloc)
+                         allocator=c.placer(2))
         patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         head = timed_steps(c, st, tgt, list(range(L)), patch, B_new)
         maybe_cpu_baseline(c, st, head)
@@ -936,7 +949,7 @@ def run_longctx8b(c: Ctx, headline: bool):
         return res, head, st
     layers = list(range(L))
     tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, n_live, arenas=2,
-                     allocator=c.alloc)
+                     allocator=c.placer(2))
     if headline:
         patch = c.big_u8(patch_capacity(S, L, cfg.blk_bytes))
         dm = torch.full((B,), -1, dtype=torch.int32)

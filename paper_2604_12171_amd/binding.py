@@ -504,6 +504,29 @@ class Arena:
                 return self.empty(numel, dtype, zone=z)
         raise PipeliveError(E_NOSPACE)
 
+    def placer(self, arenas_per_group: int):
+        """An ``allocator`` for :class:`KVRegion`: all arenas of a layer group in one class zone, so that
+        a kernel that reads one layer reads one region of the memory.  Group g goes to class g mod
+        n_classes if that zone can hold the whole group, else to the class zone with the most room that
+        can; a group is only split over zones when none can."""
+        chosen = {}
+
+        def alloc(numel, dtype, group):
+            nbytes = int(numel) * torch.empty(0, dtype=dtype).element_size()
+            z = chosen.get(group)
+            if z is None:
+                need = int(arenas_per_group) * (nbytes + 4096)
+                first = 1 + int(group) % self.n_classes
+                rest = sorted((c for c in range(1, self.n_classes + 1) if c != first), key=lambda c: -self.room(c))
+                z = next((c for c in [first] + rest if self.room(c) >= need), None)
+                if z is None:
+                    z = max(range(1, self.n_classes + 1), key=self.room)
+                chosen[group] = z
+            if self.room(z) >= nbytes:
+                return self.empty(numel, dtype, zone=z)
+            return self.empty_in_class(numel, dtype, prefer=group)
+        return alloc
+
     def close(self) -> None:
         if self.handle:
             load().pipelive_arena_destroy(self.handle)
@@ -528,8 +551,8 @@ class KVRegion:
     :class:`VmmPool` (shuffled positions); only ids below ``num_blocks`` are
     backed, :meth:`grow_backing` and :meth:`release_tail` follow a resize.
     ``allocator`` (arena backing only): ``allocator(numel, dtype, group)`` returns the 1-D device
-    tensor one arena of layer group ``group`` is laid in (e.g. :meth:`Arena.empty_in_class` with
-    ``prefer=group``); default: torch allocations."""
+    tensor one arena of layer group ``group`` is laid in (e.g. :meth:`Arena.placer`); default: torch
+    allocations."""
 
     def __init__(self, num_layers, num_q_heads, num_kv_heads, head_dim, block_tokens, num_blocks,
                  capacity_blocks=None, stack_k=1, arenas=3, fill_bits=None, device="cuda",

@@ -136,7 +136,7 @@ def test_patch_round_through_arena_memory_equals_oracle(offset):
                           fill_bits=pin.BF16_NAN)
     tgt_d = P.KVRegion(2, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B,
                        arenas=2, fill_bits=pin.BF16_NAN,
-                       allocator=lambda n, dt, g: a.empty_in_class(n, dt, prefer=g))
+                       allocator=a.placer(2))
     assert all(a.base + 6 * MiB <= t.data_ptr() < a.base + a.nbytes for t in tgt_d.arenas)   # in the class zones
     patch_h = np.zeros(cap, dtype=np.uint8)
     layers, dst_layers = [0, 1], [1, 0]

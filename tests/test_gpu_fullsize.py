@@ -384,21 +384,20 @@ def test_stage70b_placed_by_the_arena_as_the_bench_places_it():
     ids = pin.draw_dirty_ids(pin.draw_batch(cfg, SEED, num_blocks=B, stride_pad=2), SEED, 1, 0.20)
     cap = 64 + 256 + (len(ids) + 8) * (4 + L * cfg.blk_bytes)
     pool_bytes = B * L * cfg.blk_bytes
-    arena = P.Arena(2 * pool_bytes + cap + (8 << 30))
+    arena = P.Arena(2 * pool_bytes + cap + (16 << 30))
     info = arena.info()
     log(f"stage70b on an arena of {arena.nbytes >> 30} GiB: classes {info['class_pieces']}, probe {info['probe_ms']:.0f} ms")
     arena.layout(cap + (256 << 20))
-    place = lambda n, dt, g: arena.empty_in_class(n, dt, prefer=g)
-    st = Stage(cfg, B, stride_pad=2, allocator=place)
+    st = Stage(cfg, B, stride_pad=2, allocator=arena.placer(4))
     lo, hi = arena.base + arena.zones[1][0], arena.base + arena.nbytes
     assert all(lo <= t.data_ptr() < hi for t in st.region.arenas)          # every pool arena in a class zone
-    if info["n_classes"] > 1:                                              # a layer's arenas share one zone
-        for g in range(L):
-            zs = {z for t in st.region.arenas[4 * g:4 * g + 4] for z in range(1, len(arena.zones))
-                  if arena.zones[z][0] <= t.data_ptr() - arena.base < arena.zones[z][0] + arena.zones[z][1]}
-            assert len(zs) == 1, (g, zs)
+    for g in range(L):                                                     # a layer's arenas share one zone
+        zs = {z for t in st.region.arenas[4 * g:4 * g + 4] for z in range(1, len(arena.zones))
+              if arena.zones[z][0] <= t.data_ptr() - arena.base < arena.zones[z][0] + arena.zones[z][1]}
+        assert len(zs) == 1, (g, zs)
     st.check_attention(64, salt=14)
-    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3, allocator=place)
+    tgt = P.KVRegion(L, cfg.num_q_heads, cfg.num_kv_heads, cfg.head_dim, cfg.block_tokens, B, arenas=3,
+                     allocator=arena.placer(3))
     patch = arena.empty(cap)
     ids32 = torch.from_numpy(np.asarray(ids, dtype=np.int32)).cuda()
     P.pipelive_kv_mark_dirty(st.region, ids32, 7)
