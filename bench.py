@@ -75,6 +75,9 @@ def parse_args():
     ap.add_argument("--arena-reserve-gib", type=int, default=20,
                     help="device memory left outside the arena (tables, queries, workspaces, the stacked pool)")
     ap.add_argument("--arena-piece-mib", type=int, default=64, help="piece size of the arena")
+    ap.add_argument("--arena-settle-s", type=int, default=24,
+                    help="longest pause (in steps of 12 s, memory released meanwhile) before the arena is taken again "
+                         "when the driver's hand-out is mixed, as it is right after another process's exit; 0: never")
     ap.add_argument("--arena-probe-mib", type=int, default=256, help="size of the stretches the arena's probe times")
     ap.add_argument("--core-only", action="store_true",
                     help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
@@ -147,16 +150,32 @@ class Ctx:
         free_b = self.torch.cuda.mem_get_info()[0]
         if gib < 0:
             gib = max(1, (free_b >> 30) - int(self.args.arena_reserve_gib))
-        try:
-            self.arena = self.P.Arena(gib << 30, piece_bytes=int(self.args.arena_piece_mib) << 20,
-                                      probe_bytes=int(self.args.arena_probe_mib) << 20)
-        except self.P.PipeliveError as e:   # placement only: the run goes on with torch allocations
-            log(f"[arena] not created ({e}); torch allocations instead")
-            return {"arena_GiB": 0, "note": f"arena of {gib} GiB could not be created: {e}"}
+        # A process that starts within seconds of another one's exit is handed memory in which the regions
+        # alternate at a grain finer than the probe resolves (it then sees hundreds of runs of equal class instead of a handful) and
+        # which no placement can sort out; about ten seconds after the last big release the driver hands out
+        # region by region again.  So: if the hand-out looks mixed, give the memory back, wait and take it again.
+        waited = 0
+        while True:
+            try:
+                self.arena = self.P.Arena(gib << 30, piece_bytes=int(self.args.arena_piece_mib) << 20,
+                                          probe_bytes=int(self.args.arena_probe_mib) << 20)
+            except self.P.PipeliveError as e:   # placement only: the run goes on with torch allocations
+                log(f"[arena] not created ({e}); torch allocations instead")
+                return {"arena_GiB": 0, "note": f"arena of {gib} GiB could not be created: {e}"}
+            info = self.arena.info()
+            if info["n_runs"] * 32 <= info["n_pieces"] or waited + 12 > int(self.args.arena_settle_s):
+                break
+            log(f"[arena] mixed hand-out ({info['n_runs']} runs of equal class in {info['n_pieces']} pieces): "
+                f"memory released, 12 s pause, then taken again")
+            self.arena.close()
+            self.arena = None
+            time.sleep(12)
+            waited += 12
         info = self.arena.info()
-        log(f"[arena] {gib} GiB in {info['n_pieces']} pieces, classes {info['class_pieces']}, probe {info['probe_ms']:.0f} ms, "
+        log(f"[arena] {gib} GiB in {info['n_pieces']} pieces, classes {info['class_pieces']} in {info['n_runs']} runs, probe {info['probe_ms']:.0f} ms, "
             f"pair copy {info['rate_same_GBps']:.0f} (same region) / {info['rate_other_GBps']:.0f} GB/s")
         return {"arena_GiB": gib, "piece_MiB": int(self.args.arena_piece_mib), "probe_MiB": int(self.args.arena_probe_mib), **info,
+                "settle_s": waited,
                 "policy": "layer l of a pool in region l mod n_classes; patch buffers in the spread zone"}
 
     def arena_layout(self, spread_bytes):

@@ -359,6 +359,8 @@ typedef struct pipelive_arena pipelive_arena_t;
 typedef struct {
   int32_t n_pieces, n_classes;
   int32_t class_pieces[PIPELIVE_ARENA_MAX_CLASSES]; /* pieces per class */
+  int32_t n_runs;        /* runs of equal class among the pieces in the order the driver handed them out: equal to
+                            n_classes when each region came in one stretch, large when the hand-out was mixed */
   float probe_ms;        /* time the probe took (0 without probe) */
   float rate_same_GBps;  /* mean rate (read + written) of the pair copies judged "same region" ... */
   float rate_other_GBps; /* ... and of those judged "different regions"; 0 if there was no contrast */

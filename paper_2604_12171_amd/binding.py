@@ -72,7 +72,7 @@ class ReconfigPlan(C.Structure):
 
 class ArenaInfo(C.Structure):
     _fields_ = [("n_pieces", C.c_int32), ("n_classes", C.c_int32), ("class_pieces", C.c_int32 * 4),
-                ("probe_ms", C.c_float), ("rate_same_GBps", C.c_float), ("rate_other_GBps", C.c_float)]
+                ("n_runs", C.c_int32), ("probe_ms", C.c_float), ("rate_same_GBps", C.c_float), ("rate_other_GBps", C.c_float)]
 
 
 class KVState(C.Structure):
@@ -449,7 +449,7 @@ class Arena:
         i = ArenaInfo()
         _check(load().pipelive_arena_info(self.handle, C.byref(i)))
         return {"n_pieces": i.n_pieces, "n_classes": i.n_classes,
-                "class_pieces": [int(x) for x in i.class_pieces][:max(1, i.n_classes)],
+                "class_pieces": [int(x) for x in i.class_pieces][:max(1, i.n_classes)], "n_runs": i.n_runs,
                 "probe_ms": round(float(i.probe_ms), 1), "rate_same_GBps": round(float(i.rate_same_GBps), 1),
                 "rate_other_GBps": round(float(i.rate_other_GBps), 1)}
 

@@ -245,6 +245,8 @@ int32_t pipelive_arena_create(size_t bytes, size_t piece_bytes, size_t probe_byt
   }
   for (int32_t c = 0; c < PIPELIVE_ARENA_MAX_CLASSES; ++c) r->info.class_pieces[c] = 0;
   for (size_t i = 0; i < np; ++i) r->info.class_pieces[r->cls[i]]++;
+  r->info.n_runs = 1;
+  for (size_t i = 1; i < np; ++i) r->info.n_runs += r->cls[i] != r->cls[i - 1];
   const int32_t rc = pipelive_arena_layout(r, r->bytes);  // everything in the spread zone to begin with
   if (rc != PIPELIVE_OK) {
     release_all(r);

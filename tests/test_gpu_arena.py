@@ -33,6 +33,7 @@ def test_arena_is_backed_whole_and_holds_data_across_pieces(probe):
     info = a.info()
     assert info["n_pieces"] == 6 and 1 <= info["n_classes"] <= 4
     assert sum(info["class_pieces"]) == 6 and all(n > 0 for n in info["class_pieces"])
+    assert info["n_classes"] <= info["n_runs"] <= 6
     if not probe:
         assert info["n_classes"] == 1 and info["probe_ms"] == 0.0
     classes = [a.piece_class(j) for j in range(6)]                 # every class as often as the probe counted it
