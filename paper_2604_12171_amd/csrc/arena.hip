@@ -101,9 +101,8 @@ hipError_t pair_rate(pipelive_arena *r, hipEvent_t e0, hipEvent_t e1, size_t a, 
 // Classes by reference units.  Unit 0 is the first reference; the unit that copies fastest beside it is the
 // second; a unit that is clearly fast beside every reference so far (in the upper quarter of the span between the
 // slowest and the fastest rate seen beside unit 0: a unit that straddles two regions is not) becomes the next one,
-// up to PIPELIVE_ARENA_MAX_CLASSES.  Every unit then joins the
-// reference beside which its pair copy is slowest.  Without contrast beside unit 0 (spread under 6 %) there is
-// one class.
+// up to PIPELIVE_ARENA_MAX_CLASSES.  Every unit then joins the reference beside which its pair copy is slowest.
+// Without contrast beside unit 0 (spread under 6 %) there is one class.
 hipError_t classify(pipelive_arena *r) {
   const size_t ppu = r->probe_bytes / r->piece_bytes;  // pieces per unit
   const size_t nu = r->handle.size() / ppu;            // whole units; pieces behind them take the last unit's class
@@ -172,9 +171,8 @@ hipError_t classify(pipelive_arena *r) {
   for (size_t i = 0; i < r->handle.size(); ++i) r->cls[i] = ucls[std::min(i / ppu, nu - 1)];
   r->info.n_classes = (int32_t)nk;
   r->info.probe_ms = ms;
-  r->info.rate_same_GBps = nk > 1 && same_n ? (float)(same_sum / same_n / 1e9) : 0.f;
+  r->info.rate_same_GBps = same_n ? (float)(same_sum / same_n / 1e9) : 0.f;
   r->info.rate_other_GBps = other_n ? (float)(other_sum / other_n / 1e9) : 0.f;
-  if (nk == 1) r->info.rate_same_GBps = same_n ? (float)(same_sum / same_n / 1e9) : 0.f;
   return hipSuccess;
 }
 
