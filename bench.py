@@ -163,7 +163,7 @@ class Ctx:
                 log(f"[arena] not created ({e}); torch allocations instead")
                 return {"arena_GiB": 0, "note": f"arena of {gib} GiB could not be created: {e}"}
             info = self.arena.info()
-            if info["n_runs"] * 32 <= info["n_pieces"] or waited + 12 > int(self.args.arena_settle_s):
+            if info["n_runs"] <= max(16, info["n_pieces"] // 32) or waited + 12 > int(self.args.arena_settle_s):
                 break
             log(f"[arena] mixed hand-out ({info['n_runs']} runs of equal class in {info['n_pieces']} pieces): "
                 f"memory released, 12 s pause, then taken again")
