@@ -198,7 +198,7 @@ size_t pipelive_noalloc_scratch_bytes(void);
  * (PIPELIVE_E_INVAL) and its rows are not written; so does a context longer
  * than max_ctx (PIPELIVE_E_RANGE: unlike in decode it cannot be truncated, the
  * query positions depend on it).  Asynchronous.
- * The kernel hands out its work through two counters in the region's
+ * The kernel hands out its work through a few counters in the region's
  * dev_state (zero between launches; the last workgroup re-arms them, so
  * replaying a captured launch is fine): two prefill calls on the same region
  * must not run at the same time (e.g. on two streams).  After a launch that

@@ -297,7 +297,8 @@ int32_t pipelive_paged_attn_prefill(const pipelive_kv_t *kv, int32_t layer, cons
   p.num_units = (int32_t)units;
   p.num_blocks = kv->d.num_blocks;
   p.status = &dev_state(kv)->status;
-  p.ticket = &dev_state(kv)->prefill_ticket;
+  p.ticket = prefill_tickets(kv);
+  p.n_lists = 1;
   p.finished = &dev_state(kv)->prefill_finished;
   HIP_TRY(launch_attn_prefill(p, kv->d.head_dim, kv->d.block_tokens, (hipStream_t)stream));
   return PIPELIVE_OK;

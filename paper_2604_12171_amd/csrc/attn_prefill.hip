@@ -70,10 +70,17 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   const int QB = (NQ * 16) / G;  // query tokens per wave
   const int WB = 4 * QB;         // query tokens per workgroup
   const int grid = gridDim.x;
+  // Work lists: the units are dealt to NL lists by KV head (list x holds heads x, x + NL, ...), each with a ticket
+  // counter of its own.  A workgroup starts on list blockIdx.x mod NL - with NL = 8 that is the XCD the hardware
+  // places it on (workgroups go to the XCDs in turn) - so the query blocks of one (sequence, KV head) pair run
+  // on one XCD and its L2 fetches the pair's K and V once; when its list is used up a workgroup moves on to
+  // the next one.  Every list holds the same sequences, so the lists are equally long.
+  const int NL = p.n_lists, HPL = Hkv / NL;
+  const int gpl = grid / NL;  // workgroups per list (the host makes the grid a multiple of NL)
   __shared__ int mailbox;  // the ticket that thread 0 drew, for the other waves
 
-  // ---- work units: units of sequence s = Hkv * ceil(q_len / WB), ordered (s, head, block); the later
-  // query blocks of a sequence attend to more tokens and come first.  The lanes that scan the
+  // ---- work units of a list: units of sequence s = (Hkv / NL) * ceil(q_len / WB), ordered (s, head, block); the
+  // later query blocks of a sequence attend to more tokens and come first.  The lanes that scan the
   // sequences also fetch what the unit needs of its sequence (no second round trip after the search).
   struct Unit {
     int s, g, wb, q0, qlen, n;  // s < 0: no such unit
@@ -90,13 +97,13 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     }
     return sc;
   };
-  auto locate = [&](int unit, Scan first) -> Unit {
+  auto locate = [&](int unit, Scan first, int list) -> Unit {
     Unit u = {-1, 0, 0, 0, 0, 0};
     int carry = 0;  // the host keeps the number of units below 2^30
     for (int base = 0; base < S && u.s < 0; base += 64) {
       const Scan sc = base == 0 ? first : scan_issue(base);
       const int nb = sc.ql > 0 ? (sc.ql + WB - 1) / WB : 0;
-      const int units = nb * Hkv;
+      const int units = nb * HPL;
       const int inc = wave_inclusive_scan(units, lane);
       const uint64_t bal = __ballot(carry + inc > unit);  // first sequence whose range holds it
       if (bal) {
@@ -105,7 +112,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
         const uint32_t rem =
             (uint32_t)(unit - (carry + __builtin_amdgcn_readlane(inc, k) - __builtin_amdgcn_readlane(units, k)));
         u.s = base + k;
-        u.g = (int)(rem / nwb);
+        u.g = list + NL * (int)(rem / nwb);
         u.wb = (int)(nwb - 1 - rem % nwb);
         u.q0 = __builtin_amdgcn_readlane(sc.qa, k);
         u.qlen = __builtin_amdgcn_readlane(sc.ql, k);
@@ -165,6 +172,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   int cs = kChainEnd;
   int c_ticket = 0;  // thread 0: the ticket it drew
   int c_unit = -1;
+  int c_list = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % (unsigned)NL));  // the list tickets are drawn from
+  int c_spent = 0;                                                                   // lists found used up
   Unit nxt = {-1, 0, 0, 0, 0, 0};
   uint64_t nxt_addr = 0;
   uint32_t nxt_bad = 0;
@@ -179,17 +188,23 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
     o.n = __builtin_amdgcn_readfirstlane(u.n);
     return o;
   };
+  // the list at hand is used up: on to the next one (step 0 draws again), or the end after the last
+  auto list_spent = [&]() -> int {
+    c_spent = __builtin_amdgcn_readfirstlane(c_spent + 1);
+    c_list = __builtin_amdgcn_readfirstlane(c_list + 1 == NL ? 0 : c_list + 1);
+    return c_spent < NL ? 0 : kChainEnd;
+  };
   // Before the tile's arithmetic: take up what the step before fetched, fetch for the next one.
   auto chain_step = [&]() {
     int next_cs = cs;
     switch (cs) {
       case 0:  // draw a ticket
-        if (tid == 0) c_ticket = atomicAdd(p.ticket, 1);
+        if (tid == 0) c_ticket = atomicAdd(p.ticket + c_list, 1);
         break;  // chain_pass_on() moves on
       case 1:  // the ticket is in the mailbox: fetch the first 64 sequences' offsets and lengths
-        c_unit = grid + __builtin_amdgcn_readfirstlane(mailbox);
+        c_unit = gpl + __builtin_amdgcn_readfirstlane(mailbox);
         if (c_unit >= p.num_units) {
-          next_cs = kChainEnd;
+          next_cs = list_spent();
         } else {
           if (lane < S) {
             row_fetch(0, p.q_offsets + lane);
@@ -206,9 +221,9 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
           sc.ql = (int)row(1)[lane] - sc.qa;
           sc.cx = (int)row(2)[lane];
         }
-        nxt = uniform_unit(locate(c_unit, sc));
+        nxt = uniform_unit(locate(c_unit, sc, c_list));
         if (nxt.s < 0) {
-          next_cs = kChainEnd;  // beyond the last unit: so is every later ticket
+          next_cs = list_spent();  // beyond the list's last unit: so is every later ticket of it
         } else if (nxt.qlen > nxt.n) {
           next_cs = kChainReady;  // invalid unit: nothing to resolve
         } else {
@@ -252,7 +267,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   };
 
   // the first unit is the workgroup's own index; its search and addresses are waited for
-  Unit cur = uniform_unit(locate(blockIdx.x, scan_issue(0)));
+  Unit cur = uniform_unit(locate((int)blockIdx.x / NL, scan_issue(0), c_list));
   uint64_t cur_addr = 0;
   uint32_t cur_bad = 0;
   if (cur.s >= 0 && cur.qlen <= cur.n) {
@@ -662,7 +677,7 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
   if (tid == 0) {
     const int done = atomicAdd(p.finished, 1);
     if (done == grid - 1) {
-      atomicExch(p.ticket, 0);
+      for (int i = 0; i < NL; ++i) atomicExch(p.ticket + i, 0);
       atomicExch(p.finished, 0);
     }
   }
@@ -685,14 +700,24 @@ int resident_workgroups() {
   return cached;
 }
 
+// One list per XCD when the KV heads and the grid divide by the XCD count, else one list for all.  num_units
+// comes in as the bound over all heads and leaves as the bound of one list.
+PrefillParams with_lists(PrefillParams p, int grid) {
+  p.n_lists = (p.Hkv % kPrefillLists == 0 && grid % kPrefillLists == 0) ? kPrefillLists : 1;
+  p.num_units /= p.n_lists;
+  return p;
+}
+
 template <int D, int BS>
 hipError_t launch_t(const PrefillParams &p, hipStream_t st) {
   if (p.out_dtype == PIPELIVE_OUT_F32) {
     const int grid = p.num_units < resident_workgroups<D, BS, true>() ? p.num_units : resident_workgroups<D, BS, true>();
-    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, true>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, true>), dim3((unsigned)grid), dim3(256), 0, st,
+                       with_lists(p, grid));
   } else {
     const int grid = p.num_units < resident_workgroups<D, BS, false>() ? p.num_units : resident_workgroups<D, BS, false>();
-    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, false>), dim3((unsigned)grid), dim3(256), 0, st, p);
+    hipLaunchKernelGGL((attn_prefill_kernel<D, BS, kPrefillNQ, false>), dim3((unsigned)grid), dim3(256), 0, st,
+                       with_lists(p, grid));
   }
   return hipGetLastError();
 }

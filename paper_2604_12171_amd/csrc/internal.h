@@ -13,8 +13,8 @@ struct DevState {
   unsigned long long n_acc;      // tokens marked since the last complete drain
   unsigned long long t_applied;  // T_applied
   int32_t status;                // sticky: first PIPELIVE_E_* seen on the device
-  int32_t prefill_ticket;        // work distribution of the prefill kernel: both are zero whenever no
-  int32_t prefill_finished;      // prefill launch of this region is running
+  int32_t unused_;
+  int32_t prefill_finished;      // prefill kernel: workgroups that have left; zero whenever no launch is running
   int32_t mark_blocks_done;      // workgroups of the running mark launch that have set their bits
   unsigned long long n_acc_taken;  // drain: n_acc as taken before the first bitmap word was exchanged
   int32_t apply_verdict;         // apply: PIPELIVE_OK or why the patch at hand is refused as a whole
@@ -22,6 +22,12 @@ struct DevState {
 };
 static_assert(sizeof(DevState) == 64, "DevState layout");
 constexpr size_t kSnapOffset = 256;
+// The prefill kernel's work lists draw their tickets from kPrefillLists counters at byte offset kListOffset of the
+// state (one list per XCD of the part); like prefill_finished they are zero whenever no prefill launch of the
+// region is running.
+constexpr int kPrefillLists = 8;
+constexpr size_t kListOffset = 64;
+static_assert(kListOffset + kPrefillLists * sizeof(int32_t) <= kSnapOffset, "list counters fit before the snapshot");
 
 struct HostPinned {  // small pinned mailbox per handle
   int64_t plan[8];
@@ -44,6 +50,7 @@ struct pipelive_kv {
 namespace pipelive {
 
 inline DevState *dev_state(const pipelive_kv *kv) { return (DevState *)kv->d.dev_state; }
+inline int32_t *prefill_tickets(const pipelive_kv *kv) { return (int32_t *)((char *)kv->d.dev_state + kListOffset); }
 inline unsigned long long *snap_words(const pipelive_kv *kv) {
   return (unsigned long long *)((char *)kv->d.dev_state + kSnapOffset);
 }
@@ -89,10 +96,11 @@ struct PrefillParams {
   int32_t num_seqs, max_ctx;
   int32_t Hq, Hkv, G;
   float scale_log2;
-  int32_t num_units;  // an upper bound on the units (the ragged split is only known on the device)
+  int32_t num_units;  // an upper bound on the units of one list (the ragged split is only known on the device)
+  int32_t n_lists;    // work lists (set by the launch)
   int64_t num_blocks;
   int32_t *status;
-  int32_t *ticket;    // units drawn beyond the first one of every workgroup; zero between launches
+  int32_t *ticket;    // per list: units drawn beyond the first one of every workgroup; zero between launches
   int32_t *finished;  // workgroups that have left; the last one zeroes both
 };
 hipError_t launch_attn_prefill(const PrefillParams &p, int D, int BS, hipStream_t st);

@@ -627,8 +627,9 @@ __global__ __launch_bounds__(kCopyThreads) void append_kernel(AppendArgs a) {
 // also re-arms the prefill kernel's work counters (they are zero already unless a launch was cut short)
 __global__ void clear_status_kernel(DevState *st) {
   st->status = 0;
-  st->prefill_ticket = 0;
   st->prefill_finished = 0;
+  int32_t *tickets = (int32_t *)((char *)st + kListOffset);
+  for (int i = 0; i < kPrefillLists; ++i) tickets[i] = 0;
 }
 
 XferArgs make_xfer(const pipelive_kv *kv, const LayerList &layers, const int32_t *dst_map) {

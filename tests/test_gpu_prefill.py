@@ -176,7 +176,8 @@ def test_clear_status_re_arms_the_prefill_work_counters():
     rng = np.random.default_rng(3)
     q = pin.f32_to_bf16_bits(rng.standard_normal((560, 8, 64)).astype(np.float32))
     q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
-    dev.state[20:28] = 77                                  # the two counters behind n_acc, t_applied, status
+    dev.state[24:28] = 77                                  # workgroups that have left ...
+    dev.state[64:96] = 77                                  # ... and the ticket counters of the eight work lists
     P.pipelive_kv_clear_status(dev)
     out = torch.full((560, 8, 64), float("nan"), dtype=torch.float32, device="cuda")
     P.pipelive_paged_attn_prefill(dev, 0, q_d, out, torch.from_numpy(batch.table).cuda(),
@@ -187,7 +188,7 @@ def test_clear_status_re_arms_the_prefill_work_counters():
     assert np.isfinite(got).all()
     ma, rl = attn_errors(got, ref)
     assert ma <= MAX_ABS and rl <= REL_L2, (ma, rl)
-    assert int(dev.state[20:28].sum()) == 0                # re-armed again by the launch itself
+    assert int(dev.state[24:28].sum()) + int(dev.state[64:96].sum()) == 0   # re-armed again by the launch itself
 
 
 def test_prefill_bad_table_entry_sets_status_and_spares_the_others():
