@@ -6,11 +6,13 @@
 // w of the workgroup that takes it owns the QB tokens [w*QB, (w+1)*QB) of the
 // block.  A wave's NQ*16 score columns are its QB tokens x the G query heads of
 // the KV head (column = token * G + head).  The kernel is persistent: as many
-// workgroups as the device holds at once; each takes the unit of its own index
-// first and then draws units from a ticket counter, and while it works on one
-// unit it already draws, searches and resolves the next (one step per tile, the
-// loads going straight into a few LDS rows), so that a unit starts with its
-// block addresses in hand.  For a unit the workgroup walks the 32-token KV
+// workgroups as the device holds at once.  The units are dealt to work lists
+// by KV head, one list per XCD, so that the query blocks of a (sequence, KV
+// head) pair share one L2; a workgroup takes a unit of its XCD's list first
+// and then draws units from that list's ticket counter (from the next list's
+// once its own is used up), and while it works on one unit it already draws,
+// searches and resolves the next (one step per tile, the loads going straight
+// into a few LDS rows), so that a unit starts with its block addresses in hand.  For a unit the workgroup walks the 32-token KV
 // tiles that its last query may see; each tile's K and V of the KV head (two
 // contiguous runs of the in-block layout) are copied once from global memory
 // into a ring of three LDS stages by LDS-direct loads (global_load_lds_dwordx4:
@@ -684,8 +686,8 @@ __global__ __launch_bounds__(256, 2) void attn_prefill_kernel(PrefillParams p) {
 }
 
 // Persistent launch: as many workgroups as the device holds at once (never more than there are
-// units); each takes the unit of its own index first and draws the following ones from the ticket
-// counter.
+// units); each takes a unit of its list first and draws the following ones from the lists' ticket
+// counters.
 template <int D, int BS, bool PAIR>
 int resident_workgroups() {
   static int cached = 0;
