@@ -78,7 +78,7 @@ def parse_args():
     ap.add_argument("--arena-settle-s", type=int, default=24,
                     help="longest pause (in steps of 12 s, memory released meanwhile) before the arena is taken again "
                          "when the driver's hand-out is mixed, as it is right after another process's exit; 0: never")
-    ap.add_argument("--arena-probe-mib", type=int, default=256, help="size of the stretches the arena's probe times")
+    ap.add_argument("--arena-probe-mib", type=int, default=1024, help="size of the stretches the arena's probe times")
     ap.add_argument("--core-only", action="store_true",
                     help="profiling aid: skip the legs outside decode, patch and resize (slot patches, prefill, "
                          "stacked pool, 4-layer rounds, sparse pool)")
@@ -163,7 +163,8 @@ class Ctx:
                 log(f"[arena] not created ({e}); torch allocations instead")
                 return {"arena_GiB": 0, "note": f"arena of {gib} GiB could not be created: {e}"}
             info = self.arena.info()
-            if info["n_runs"] <= max(16, info["n_pieces"] // 32) or waited + 12 > int(self.args.arena_settle_s):
+            n_stretches = info["n_pieces"] * int(self.args.arena_piece_mib) // int(self.args.arena_probe_mib)
+            if info["n_runs"] <= max(8, n_stretches // 8) or waited + 12 > int(self.args.arena_settle_s):
                 break
             log(f"[arena] mixed hand-out ({info['n_runs']} runs of equal class in {info['n_pieces']} pieces): "
                 f"memory released, 12 s pause, then taken again")

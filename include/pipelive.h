@@ -338,14 +338,16 @@ uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *pool);
  * piece_bytes  a multiple of 2 MiB (E_INVAL otherwise): the grain at which the
  *              spread zone alternates between the classes; 64 MiB in the bench
  * probe_bytes  0: no probe, one class.  Otherwise a multiple of piece_bytes
- *              (E_INVAL otherwise): 256 MiB in the bench; the probe's launches
- *              go over a stretch until 512 MiB have moved, so that short
- *              stretches can still be timed, but below 64 MiB the classes
- *              found are noise (harmless: only the order of the pieces depends
- *              on them).  About 4 ms per GiB of the range: device work on the
- *              null stream, the call returns when it is done; the device
- *              should be idle otherwise.  A range shorter than two such
- *              stretches is not probed
+ *              (E_INVAL otherwise): 1 GiB in the bench.  Shorter stretches
+ *              resolve a finer mix of regions but are harder to time (the
+ *              probe's launches go over a stretch until 512 MiB have moved;
+ *              256 MiB still classifies cleanly on an idle device, not under
+ *              a tracing profiler; below 64 MiB the classes found are noise,
+ *              which is harmless: only the order of the pieces depends on
+ *              them).  About 2 ms per GiB of the range at 1 GiB, 4 ms at
+ *              256 MiB: device work on the null stream, the call returns when
+ *              it is done; the device should be idle otherwise.  A range
+ *              shorter than two such stretches is not probed
  * spread_bytes rounded up to whole pieces, at most the range
  * E_NOSPACE if the device is out of memory, E_HIP for any other runtime error;
  * nothing of a failing create stays allocated (after a failing layout the

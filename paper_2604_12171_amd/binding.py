@@ -435,7 +435,7 @@ class Arena:
     1 + c: region c only).  The tensors are views without ownership: keep the arena alive, and do
     not call :meth:`layout` again, as long as they are in use."""
 
-    def __init__(self, nbytes: int, piece_bytes: int = 64 << 20, probe_bytes: int = 256 << 20):
+    def __init__(self, nbytes: int, piece_bytes: int = 64 << 20, probe_bytes: int = 1 << 30):
         h = C.c_void_p()
         _check(load().pipelive_arena_create(int(nbytes), int(piece_bytes), int(probe_bytes), C.byref(h)))
         self.handle = h

@@ -98,11 +98,11 @@ hipError_t pair_rate(pipelive_arena *r, hipEvent_t e0, hipEvent_t e1, size_t a, 
   return hipSuccess;
 }
 
-// Classes by reference units.  Unit 0 is the first reference; the unit that copies fastest beside it is the
-// second; a unit that is clearly fast beside every reference so far (in the upper quarter of the span between the
-// slowest and the fastest rate seen beside unit 0: a unit that straddles two regions is not) becomes the next one,
+// Classes by reference units.  The first reference is unit 0 (or, if nothing contrasts beside it, one of a few
+// others); the unit that copies fastest beside it is the second; a unit that is clearly fast beside every reference so far (in the upper quarter of the span between the
+// slowest and the fastest rate seen beside the first: a unit that straddles two regions is not) becomes the next one,
 // up to PIPELIVE_ARENA_MAX_CLASSES.  Every unit then joins the reference beside which its pair copy is slowest.
-// Without contrast beside unit 0 (spread under 6 %) there is one class.
+// Without contrast (spread under 6 %) beside any of the tried first references there is one class.
 hipError_t classify(pipelive_arena *r) {
   const size_t ppu = r->probe_bytes / r->piece_bytes;  // pieces per unit
   const size_t nu = r->handle.size() / ppu;            // whole units; pieces behind them take the last unit's class
@@ -120,29 +120,44 @@ hipError_t classify(pipelive_arena *r) {
     for (size_t i = 0; i < nu && e == hipSuccess; ++i)
       if (i != u) e = pair_rate(r, e0, e1, u, i, &rate.back()[i]);
   };
+  // The first reference has to lie inside one region: a unit that straddles two shows no contrast.  Unit 0 is
+  // tried first, then a few others; if none shows contrast there is one class.
   double thr = 0;
-  if (e == hipSuccess) add_ref(0);
-  if (e == hipSuccess) {
-    double lo = rate[0][1], hi = rate[0][1];
-    size_t fastest = 1;
-    for (size_t i = 1; i < nu; ++i) {
-      if (rate[0][i] < lo) lo = rate[0][i];
-      if (rate[0][i] > hi) hi = rate[0][i], fastest = i;
+  const size_t candidates[5] = {0, nu / 2, nu - 1, nu / 4, (3 * nu) / 4};
+  bool contrast = false;
+  size_t fastest = 0;
+  for (int c = 0; c < 5 && e == hipSuccess && !contrast; ++c) {
+    const size_t u = candidates[c];
+    bool tried = false;
+    for (int k = 0; k < c; ++k) tried |= candidates[k] == u;
+    if (tried) continue;
+    ref.clear();
+    rate.clear();
+    add_ref(u);
+    if (e != hipSuccess) break;
+    double lo = 0, hi = 0;
+    bool any = false;
+    for (size_t i = 0; i < nu; ++i) {
+      if (i == u) continue;
+      if (!any || rate[0][i] < lo) lo = rate[0][i];
+      if (!any || rate[0][i] > hi) hi = rate[0][i], fastest = i;
+      any = true;
     }
     thr = lo + 0.75 * (hi - lo);
-    if (hi - lo >= 0.06 * hi) {
-      add_ref(fastest);
-      while (e == hipSuccess && (int32_t)ref.size() < PIPELIVE_ARENA_MAX_CLASSES) {
-        size_t best = 0;
-        double best_min = 0;
-        for (size_t i = 0; i < nu; ++i) {
-          double m = rate[0][i];
-          for (size_t k = 1; k < ref.size(); ++k) m = std::min(m, rate[k][i]);
-          if (m > best_min) best_min = m, best = i;  // a reference has rate 0 beside itself and is never picked
-        }
-        if (best_min <= thr) break;
-        add_ref(best);
+    contrast = hi - lo >= 0.06 * hi;
+  }
+  if (e == hipSuccess && contrast) {
+    add_ref(fastest);
+    while (e == hipSuccess && (int32_t)ref.size() < PIPELIVE_ARENA_MAX_CLASSES) {
+      size_t best = 0;
+      double best_min = 0;
+      for (size_t i = 0; i < nu; ++i) {
+        double m = rate[0][i];
+        for (size_t k = 1; k < ref.size(); ++k) m = std::min(m, rate[k][i]);
+        if (m > best_min) best_min = m, best = i;  // a reference has rate 0 beside itself and is never picked
       }
+      if (best_min <= thr) break;
+      add_ref(best);
     }
   }
   float ms = 0.f;
