@@ -355,7 +355,12 @@ uint64_t pipelive_vmm_pool_base(const pipelive_vmm_pool_t *pool);
  * serving loop: create and layout wait for the device and are host-side driver
  * calls of the order of a millisecond per piece.  The contents of the range
  * are undefined after either; no kernel may be using the range during layout
- * or destroy, which unmaps and releases everything. */
+ * or destroy, which unmaps and releases everything.
+ * For some seconds after a process has released a few hundred GB the driver
+ * hands memory out with the regions mixed at a grain no probe resolves; n_runs
+ * in the info shows it (dozens to hundreds instead of n_classes).  A caller
+ * that sees it can destroy the arena, wait about ten seconds and create it
+ * again. */
 #define PIPELIVE_ARENA_MAX_CLASSES 4
 typedef struct pipelive_arena pipelive_arena_t;
 typedef struct {
