@@ -35,7 +35,8 @@ CASES = [
 
 
 @pytest.mark.parametrize("shape", [(4, 2, 64, 16), (32, 8, 128, 16), (64, 8, 128, 16), (16, 1, 128, 32),
-                                   (8, 8, 64, 32), (6, 2, 128, 16), (32, 8, 128, 128), (4, 2, 64, 64)])
+                                   (8, 8, 64, 32), (6, 2, 128, 16), (32, 8, 128, 128), (4, 2, 64, 64),
+                                   (32, 16, 64, 16)])     # 16 KV heads: two heads per work list
 @pytest.mark.parametrize("case", range(len(CASES)))
 def test_prefill_matches_oracle(shape, case):
     Hq, Hkv, D, bs = shape
