@@ -129,12 +129,13 @@ def test_prefill_many_sequences_multi_chunk_unit_search():
     assert P.pipelive_kv_read_state(dev).status == 0
 
 
-def test_prefill_more_units_than_resident_workgroups_and_relaunch():
+@pytest.mark.parametrize("Hkv", [4, 8])                    # one work list for all / one per XCD, dealt by KV head
+def test_prefill_more_units_than_resident_workgroups_and_relaunch(Hkv):
     """Enough (sequence, head, query block) units that every resident workgroup has to draw further
-    ones from the ticket counter (ragged lengths, chunks and full prompts); a second launch must find
+    ones from the ticket counters (ragged lengths, chunks and full prompts); a second launch must find
     the counters re-armed and give the same bits."""
     rng = np.random.default_rng(11)
-    S, Hq, Hkv, D, bs = 100, 16, 4, 64, 16                # more than 64 sequences: the drawn units' search spans chunks
+    S, Hq, D, bs = 100, 16, 64, 16                        # more than 64 sequences: the drawn units' search spans chunks
     ctx = rng.integers(60, 260, size=S)
     qlen = np.where(rng.random(S) < 0.5, ctx, np.minimum(ctx, rng.integers(1, 120, size=S)))
     qlen[5::17] = 0
@@ -144,7 +145,8 @@ def test_prefill_more_units_than_resident_workgroups_and_relaunch():
     fill_pair(cfg, batch, SEED, host, dev)
     qo = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
     total_q = int(qo[-1])
-    units = Hkv * int(np.sum((qlen + 31) // 32))          # 32 query tokens per unit at G = 4
+    wb = 4 * (32 // (Hq // Hkv))                          # query tokens per unit
+    units = Hkv * int(np.sum((qlen + wb - 1) // wb))
     assert units > 2 * 256 * 2                            # more than two per resident workgroup
     q = pin.f32_to_bf16_bits(rng.standard_normal((total_q, Hq, D)).astype(np.float32))
     q_d = torch.from_numpy(q.view(np.int16)).cuda().view(torch.bfloat16)
