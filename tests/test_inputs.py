@@ -70,3 +70,15 @@ def test_dirty_ids_include_last_blocks():
     assert set(d).issubset(set(bt.live_ids))
     f = pin.geometric_fractions(0.20, 0.01, 6)
     assert abs(f[0] - 0.2) < 1e-12 and abs(f[-1] - 0.01) < 1e-12
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py is a one-GPU program: --gpus N with N > 1 exits with a message before it touches a device"""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
