@@ -136,7 +136,7 @@ class Ctx:
         gc.collect()
         self.torch.cuda.empty_cache()
 
-    # ---- Placement: pools and patch buffers are carved out of one region-aware arena (pieces of 1 GiB that
+    # ---- Placement: pools and patch buffers are carved out of one region-aware arena (pieces of 64 MiB that
     # the library sorts by the region of the device memory they lie in).  The KV blocks of a layer go into one
     # region, consecutive layers into different ones: a decode launch then reads one region, and the copies,
     # which work on all layers at once, use all of them.  Patch buffers go into the spread zone, whose pieces
